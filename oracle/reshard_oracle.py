@@ -1,0 +1,412 @@
+"""Plain CPU oracle: reshard training state by gathering every source shard into
+the full logical tensors and re-splitting them for the target world.
+
+TEST INFRASTRUCTURE ONLY -- never imported by the product path.  No blocking, no
+fusion, no descriptor planning: this file is the *definition* of the result.
+
+What the paper fixes (LiveR, Section 4.6 and Appendix A.2):
+  * the state is a set of logical tensors plus a sharding specification that is
+    independent of rank numbering (Abstract Resource View, Section 4.6.1);
+  * a reshard is correct iff the union of all shards is the same before and
+    after (Appendix A.2.1, Eq. 1) and every element of the global state appears
+    exactly once in the new configuration (Section 4.6, constraint 1);
+  * the paper's own check is "aggregate the global tensors and compare
+    element-wise" with deviation exactly zero (Section 6.6).
+So the result has a plain definition: gather, then split.  This file writes that
+definition out.
+
+What the paper does NOT fix, and the readings taken here (each is a convention of
+Megatron-style mixed-parallel training, stated so a reader can check it by eye):
+  R1  logical tensors are stored row-major as [out_features, in_features].
+  R2  column-parallel linears (q/k/v, gate/up, embeddings, lm_head) are split in
+      contiguous blocks of dim 0; row-parallel linears (o, down) in contiguous
+      blocks of dim 1; norms, position embeddings and the biases of row-parallel
+      linears are replicated on every TP rank.
+  R3  q, k, v live in ONE fused physical parameter per rank, grouped per
+      kv-head group g: [q rows of the group ; k rows of g ; v rows of g], groups
+      in ascending order (MHA: per head [q_h; k_h; v_h]).
+  R4  with a gated FFN, gate and up live in one physical parameter per rank as
+      [gate rows of this rank ; up rows of this rank].
+  R5  a (tp, pp) rank's parameters are flattened row-major and packed back to
+      back, in forward order, into one flat buffer; the bf16 and fp32 buffers
+      use the same element offsets.
+  R6  the flat buffer is zero-padded to N_pad, a multiple of DP*pad_multiple;
+      PARAM (bf16) is a full N_pad copy on every DP rank; MASTER / ADAM_M /
+      ADAM_V (fp32) are split evenly: DP rank d owns [d*S, (d+1)*S), S=N_pad/DP.
+  R7  where a value exists more than once in the source world, the copy that is
+      read is the one with the lowest coordinate (dp=0, tp=0, first stage).
+  R8  with tied embeddings and PP>1 the last stage holds a second physical copy
+      of the word embedding (same TP split) after the final norm.
+  R9  stage pp owns layers [pp*L/PP, (pp+1)*L/PP).
+  R10 fp32 -> bf16 is round-to-nearest-even on the upper 16 bits; NaN keeps sign
+      and upper payload and gets the quiet bit.
+  R12 buffer-table index of a rank is tp + TP*(dp + DP*pp).
+
+All data are handled as raw bit patterns (uint16 for bf16, uint32 for fp32):
+resharding moves bits, it never interprets them (except rne_bf16).
+
+Pins (tests/test_oracle_*.py): closed-form sizes, index-encoded tensors against
+formulas typed out in the test, brute-force per-element ownership on tiny models,
+identity / round trip / composition, the TP4->TP8 worked example of Section
+4.6.1, and torch's CPU float->bfloat16 conversion for rne_bf16.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Callable, Dict, Iterable, List, Optional, Tuple
+
+import numpy as np
+
+PARAM, MASTER, ADAM_M, ADAM_V = 0, 1, 2, 3
+KINDS = (PARAM, MASTER, ADAM_M, ADAM_V)
+WORD = {PARAM: np.uint16, MASTER: np.uint32, ADAM_M: np.uint32, ADAM_V: np.uint32}
+
+
+@dataclass(frozen=True)
+class ModelSpec:
+    n_layers: int
+    hidden: int
+    n_q_heads: int
+    n_kv_heads: int
+    ffn: int
+    vocab: int
+    max_pos: int = 0          # 0: no learned position embedding
+    glu: bool = False         # gated FFN (SwiGLU): gate + up
+    norm_bias: bool = False   # LayerNorm (with bias) instead of RMSNorm
+    linear_bias: bool = False
+    tied_embed: bool = False  # no lm_head; output layer reuses embed.word
+
+
+@dataclass(frozen=True)
+class Layout:
+    tp: int
+    pp: int
+    dp: int
+    pad_multiple: int = 128
+
+    @property
+    def n_ranks(self) -> int:
+        return self.tp * self.pp * self.dp
+
+    def rank(self, tp: int, pp: int, dp: int) -> int:       # R12
+        return tp + self.tp * (dp + self.dp * pp)
+
+
+def check_supported(spec: ModelSpec, lay: Layout) -> None:
+    ok = (spec.n_layers % lay.pp == 0 and spec.hidden % spec.n_q_heads == 0
+          and spec.n_q_heads % spec.n_kv_heads == 0 and spec.n_kv_heads % lay.tp == 0
+          and spec.ffn % lay.tp == 0 and spec.vocab % lay.tp == 0
+          and min(lay.tp, lay.pp, lay.dp, lay.pad_multiple) >= 1)
+    if not ok:
+        raise ValueError(f"unsupported combination {spec} {lay}")
+
+
+# --------------------------------------------------------------------------- R1
+def logical_tensors(spec: ModelSpec) -> Dict[str, Tuple[int, ...]]:
+    """Name -> shape of every logical tensor, in forward order."""
+    H, F, V = spec.hidden, spec.ffn, spec.vocab
+    hd = H // spec.n_q_heads
+    Q, KV = spec.n_q_heads * hd, spec.n_kv_heads * hd
+    t: Dict[str, Tuple[int, ...]] = {"embed.word": (V, H)}
+    if spec.max_pos:
+        t["embed.pos"] = (spec.max_pos, H)
+    for l in range(spec.n_layers):
+        p = f"L{l}."
+        t[p + "ln1.w"] = (H,)
+        if spec.norm_bias:
+            t[p + "ln1.b"] = (H,)
+        t[p + "q.w"], t[p + "k.w"], t[p + "v.w"] = (Q, H), (KV, H), (KV, H)
+        if spec.linear_bias:
+            t[p + "q.b"], t[p + "k.b"], t[p + "v.b"] = (Q,), (KV,), (KV,)
+        t[p + "o.w"] = (H, Q)
+        if spec.linear_bias:
+            t[p + "o.b"] = (H,)
+        t[p + "ln2.w"] = (H,)
+        if spec.norm_bias:
+            t[p + "ln2.b"] = (H,)
+        if spec.glu:
+            t[p + "gate.w"] = (F, H)
+        t[p + "up.w"] = (F, H)
+        if spec.linear_bias:
+            if spec.glu:
+                t[p + "gate.b"] = (F,)
+            t[p + "up.b"] = (F,)
+        t[p + "down.w"] = (H, F)
+        if spec.linear_bias:
+            t[p + "down.b"] = (H,)
+    t["final_norm.w"] = (H,)
+    if spec.norm_bias:
+        t["final_norm.b"] = (H,)
+    if not spec.tied_embed:
+        t["lm_head.w"] = (V, H)
+    return t
+
+
+# ------------------------------------------------------------- physical params
+@dataclass(frozen=True)
+class Block:
+    """local[loc] holds logical[name][idx] (tuples of slices)."""
+    name: str
+    idx: Tuple[slice, ...]
+    loc: Tuple[slice, ...]
+
+
+@dataclass
+class PhysParam:
+    name: str
+    shape: Tuple[int, ...]
+    blocks: List[Block]
+    canonical: bool           # R7: is this rank's copy the one a gather reads?
+    offset: int = 0           # element offset in the (tp, pp) flat buffer
+
+    @property
+    def size(self) -> int:
+        return int(np.prod(self.shape))
+
+
+@dataclass
+class StageView:
+    params: List[PhysParam]
+    n_local: int
+    n_pad: int
+    S: int                    # elements per DP slice of the fp32 buffers
+
+
+def _rows(a: int, b: int) -> Tuple[slice, ...]:
+    return (slice(a, b),)
+
+
+def _cols(a: int, b: int) -> Tuple[slice, ...]:
+    return (slice(None), slice(a, b))
+
+
+_ALL: Tuple[slice, ...] = (slice(None),)
+
+
+def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int) -> StageView:
+    """Ordered physical parameters of rank column (tp, pp) -- R2..R5, R8, R9."""
+    check_supported(spec, lay)
+    shapes = logical_tensors(spec)
+    TP = lay.tp
+    hd = spec.hidden // spec.n_q_heads
+    qpg = spec.n_q_heads // spec.n_kv_heads          # q heads per kv group
+    g_loc = spec.n_kv_heads // TP                    # kv groups per TP rank
+    out: List[PhysParam] = []
+
+    def replicated(name: str) -> None:               # R2: full copy on every tp
+        out.append(PhysParam(name, shapes[name], [Block(name, _ALL, _ALL)], tp == 0))
+
+    def split0(phys: str, name: str, canonical: bool = True) -> None:   # R2 column-parallel
+        n = shapes[name][0] // TP
+        out.append(PhysParam(phys, (n,) + shapes[name][1:],
+                             [Block(name, _rows(tp * n, (tp + 1) * n), _ALL)], canonical))
+
+    def split1(phys: str, name: str) -> None:        # R2 row-parallel
+        r, c = shapes[name]
+        n = c // TP
+        out.append(PhysParam(phys, (r, n), [Block(name, _cols(tp * n, (tp + 1) * n), _ALL)], True))
+
+    def fused_qkv(p: str, suffix: str) -> None:      # R3
+        tail = shapes[p + "q." + suffix][1:]
+        blocks, row = [], 0
+        for j in range(g_loc):
+            g = tp * g_loc + j
+            for nm, lo, n in ((p + "q." + suffix, g * qpg * hd, qpg * hd),
+                              (p + "k." + suffix, g * hd, hd),
+                              (p + "v." + suffix, g * hd, hd)):
+                blocks.append(Block(nm, _rows(lo, lo + n), _rows(row, row + n)))
+                row += n
+        out.append(PhysParam(p + "qkv." + suffix, (row,) + tail, blocks, True))
+
+    def fc1(p: str, suffix: str) -> None:            # R4
+        if not spec.glu:
+            split0(p + "fc1." + suffix, p + "up." + suffix)
+            return
+        n = spec.ffn // TP
+        tail = shapes[p + "up." + suffix][1:]
+        out.append(PhysParam(p + "fc1." + suffix, (2 * n,) + tail,
+                             [Block(p + "gate." + suffix, _rows(tp * n, (tp + 1) * n), _rows(0, n)),
+                              Block(p + "up." + suffix, _rows(tp * n, (tp + 1) * n), _rows(n, 2 * n))],
+                             True))
+
+    per_stage = spec.n_layers // lay.pp              # R9
+    if pp == 0:
+        split0("embed.word", "embed.word")
+        if spec.max_pos:
+            replicated("embed.pos")
+    for l in range(pp * per_stage, (pp + 1) * per_stage):
+        p = f"L{l}."
+        replicated(p + "ln1.w")
+        if spec.norm_bias:
+            replicated(p + "ln1.b")
+        fused_qkv(p, "w")
+        if spec.linear_bias:
+            fused_qkv(p, "b")
+        split1(p + "o.w", p + "o.w")
+        if spec.linear_bias:
+            replicated(p + "o.b")
+        replicated(p + "ln2.w")
+        if spec.norm_bias:
+            replicated(p + "ln2.b")
+        fc1(p, "w")
+        if spec.linear_bias:
+            fc1(p, "b")
+        split1(p + "fc2.w", p + "down.w")
+        if spec.linear_bias:
+            replicated(p + "down.b")
+    if pp == lay.pp - 1:
+        replicated("final_norm.w")
+        if spec.norm_bias:
+            replicated("final_norm.b")
+        if not spec.tied_embed:
+            split0("lm_head.w", "lm_head.w")
+        elif lay.pp > 1:                             # R8: second copy, never the one read
+            split0("embed.word(tied copy)", "embed.word", canonical=False)
+
+    off = 0
+    for prm in out:                                  # R5: back to back, no per-param padding
+        prm.offset = off
+        off += prm.size
+    quantum = lay.dp * lay.pad_multiple              # R6
+    n_pad = -(-off // quantum) * quantum
+    return StageView(out, off, n_pad, n_pad // lay.dp)
+
+
+def buffer_elems(spec: ModelSpec, lay: Layout, tp: int, pp: int, kind: int) -> int:
+    sv = stage_view(spec, lay, tp, pp)
+    return sv.n_pad if kind == PARAM else sv.S
+
+
+# ------------------------------------------------------------------ flat access
+Reader = Callable[[int, int, int, int], np.ndarray]   # (rank, kind, lo, hi) -> elements [lo, hi)
+
+
+def dict_reader(bufs: Dict[Tuple[int, int], np.ndarray]) -> Reader:
+    return lambda rank, kind, lo, hi: bufs[(rank, kind)][lo:hi]
+
+
+def read_flat(read: Reader, lay: Layout, tp: int, pp: int, kind: int, lo: int, hi: int, S: int,
+              dp_replica: int = 0) -> np.ndarray:
+    """Elements [lo, hi) of the (tp, pp) flat buffer of `kind` -- R6.
+
+    PARAM: taken from replica `dp_replica`.  fp32 kinds: concatenation of the
+    pieces held by the DP ranks whose slices [d*S, (d+1)*S) overlap [lo, hi)."""
+    if kind == PARAM:
+        return np.asarray(read(lay.rank(tp, pp, dp_replica), kind, lo, hi))
+    parts = []
+    for d in range(lay.dp):
+        a, b = max(lo, d * S), min(hi, (d + 1) * S)
+        if a < b:
+            parts.append(np.asarray(read(lay.rank(tp, pp, d), kind, a - d * S, b - d * S)))
+    return np.concatenate(parts) if parts else np.empty(0, WORD[kind])
+
+
+# ----------------------------------------------------------------------- gather
+def gather_logical(spec: ModelSpec, lay: Layout, kind: int, read: Reader,
+                   names: Optional[Iterable[str]] = None, check: bool = True) -> Dict[str, np.ndarray]:
+    """Full logical tensors (all, or `names`) of `kind` from a sharded world.
+
+    Each canonical physical parameter is cut out of its rank's flat buffer,
+    reshaped to its local shape and assigned into the logical tensors block by
+    block.  With `check`, every logical element must be assigned exactly once
+    (Appendix A.2.1, Eq. 1: the shards of a configuration tile the tensor)."""
+    shapes = logical_tensors(spec)
+    want = set(shapes) if names is None else set(names)
+    logical = {n: np.zeros(shapes[n], WORD[kind]) for n in shapes if n in want}
+    hits = {n: np.zeros(shapes[n], np.uint8) for n in logical} if check else None
+    for pp in range(lay.pp):
+        for tp in range(lay.tp):
+            sv = stage_view(spec, lay, tp, pp)
+            for prm in sv.params:
+                if not prm.canonical or not any(b.name in want for b in prm.blocks):
+                    continue
+                local = read_flat(read, lay, tp, pp, kind, prm.offset, prm.offset + prm.size,
+                                  sv.S).reshape(prm.shape)
+                for b in prm.blocks:
+                    if b.name in want:
+                        logical[b.name][b.idx] = local[b.loc]
+                        if hits is not None:
+                            hits[b.name][b.idx] += 1
+    if hits is not None:
+        for n, h in hits.items():
+            if not (h == 1).all():
+                raise AssertionError(f"logical tensor {n}: not every element gathered exactly once")
+    return logical
+
+
+# ------------------------------------------------------------------------ split
+def build_shard(prm: PhysParam, logical: Dict[str, np.ndarray]) -> np.ndarray:
+    """Local shard of one physical parameter, cut out of the logical tensors."""
+    dtype = logical[prm.blocks[0].name].dtype
+    local = np.zeros(prm.shape, dtype)
+    for b in prm.blocks:
+        local[b.loc] = logical[b.name][b.idx]
+    return local
+
+
+def split_logical(spec: ModelSpec, lay: Layout, kind: int,
+                  logical: Dict[str, np.ndarray]) -> Dict[Tuple[int, int], np.ndarray]:
+    """Every rank's buffer of `kind` for world `lay`; padding is +0 (R6)."""
+    out: Dict[Tuple[int, int], np.ndarray] = {}
+    for pp in range(lay.pp):
+        for tp in range(lay.tp):
+            sv = stage_view(spec, lay, tp, pp)
+            flat = np.zeros(sv.n_pad, WORD[kind])
+            for prm in sv.params:
+                flat[prm.offset:prm.offset + prm.size] = build_shard(prm, logical).ravel()
+            for dp in range(lay.dp):
+                if kind == PARAM:
+                    out[(lay.rank(tp, pp, dp), kind)] = flat.copy()
+                else:
+                    out[(lay.rank(tp, pp, dp), kind)] = flat[dp * sv.S:(dp + 1) * sv.S].copy()
+    return out
+
+
+# ------------------------------------------------------------------------- cast
+def rne_bf16(u: np.ndarray) -> np.ndarray:
+    """fp32 bit patterns -> bf16 bit patterns, round to nearest even (R10)."""
+    u = np.asarray(u, np.uint32)
+    wide = u.astype(np.uint64)
+    rounded = ((wide + 0x7FFF + ((wide >> 16) & 1)) >> 16).astype(np.uint16)
+    is_nan = (u & 0x7FFFFFFF) > 0x7F800000
+    quiet = ((u >> 16) | 0x0040).astype(np.uint16)
+    return np.where(is_nan, quiet, rounded)
+
+
+# ---------------------------------------------------------------------- reshard
+def reshard_state(spec: ModelSpec, src: Layout, dst: Layout,
+                  src_bufs: Dict[Tuple[int, int], np.ndarray], derive_bf16: bool = False,
+                  kinds: Iterable[int] = KINDS) -> Dict[Tuple[int, int], np.ndarray]:
+    """The whole result: gather under `src`, split under `dst`, kind by kind.
+
+    derive_bf16: target PARAM is rne_bf16 of the gathered MASTER tensors (the
+    element with the same logical index), not a copy of the source PARAM."""
+    read = dict_reader(src_bufs)
+    out: Dict[Tuple[int, int], np.ndarray] = {}
+    for kind in kinds:
+        if kind == PARAM and derive_bf16:
+            master = gather_logical(spec, src, MASTER, read)
+            logical = {n: rne_bf16(a) for n, a in master.items()}
+        else:
+            logical = gather_logical(spec, src, kind, read)
+        out.update(split_logical(spec, dst, kind, logical))
+    return out
+
+
+def expected_shards(spec: ModelSpec, lay: Layout, logical: Dict[str, np.ndarray]):
+    """For a subset of logical tensors: yield (tp, pp, stage_view, param, shard)
+    for every physical parameter of world `lay` built only from that subset.
+    Lets a caller verify a few tensors of a very large state one at a time."""
+    have = set(logical)
+    for pp in range(lay.pp):
+        for tp in range(lay.tp):
+            sv = stage_view(spec, lay, tp, pp)
+            for prm in sv.params:
+                if all(b.name in have for b in prm.blocks):
+                    yield tp, pp, sv, prm, build_shard(prm, logical)
+
+
+__all__ = ["PARAM", "MASTER", "ADAM_M", "ADAM_V", "KINDS", "WORD", "ModelSpec", "Layout",
+           "check_supported", "logical_tensors", "Block", "PhysParam", "StageView", "stage_view",
+           "buffer_elems", "Reader", "dict_reader", "read_flat", "gather_logical", "build_shard",
+           "split_logical", "rne_bf16", "reshard_state", "expected_shards"]

@@ -1,0 +1,148 @@
+"""Per-element ownership, typed out as integer arithmetic (test tool).
+
+For element `k` of physical parameter `phys` on TP rank `tp`, which logical
+tensor and which row-major index inside it does that element hold?  These are
+the closed forms of the layout conventions (column-parallel: contiguous rows;
+row-parallel: a strip of every row; fused QKV grouped per kv-head group; gated
+FFN stored as [gate rows ; up rows] per rank).  Nothing here slices arrays or
+calls the oracle: it exists so that the oracle's slicing can be checked against
+formulas a reader can verify with pencil and paper.
+"""
+import numpy as np
+
+
+def dims(spec):
+    H = spec.hidden
+    hd = H // spec.n_q_heads
+    return H, hd, spec.n_q_heads * hd, spec.n_kv_heads * hd, spec.ffn, spec.vocab
+
+
+def layer_param_sizes(spec, TP, l):
+    """[(physical name, element count)] of one transformer layer on one TP rank."""
+    H, hd, Q, KV, F, V = dims(spec)
+    p = f"L{l}."
+    out = [(p + "ln1.w", H)]
+    if spec.norm_bias:
+        out.append((p + "ln1.b", H))
+    out.append((p + "qkv.w", (Q + 2 * KV) * H // TP))
+    if spec.linear_bias:
+        out.append((p + "qkv.b", (Q + 2 * KV) // TP))
+    out.append((p + "o.w", H * Q // TP))
+    if spec.linear_bias:
+        out.append((p + "o.b", H))
+    out.append((p + "ln2.w", H))
+    if spec.norm_bias:
+        out.append((p + "ln2.b", H))
+    n_fc1 = 2 * F if spec.glu else F
+    out.append((p + "fc1.w", n_fc1 * H // TP))
+    if spec.linear_bias:
+        out.append((p + "fc1.b", n_fc1 // TP))
+    out.append((p + "fc2.w", H * F // TP))
+    if spec.linear_bias:
+        out.append((p + "down.b", H))
+    return out
+
+
+def stage_param_sizes(spec, TP, PP, pp):
+    H, hd, Q, KV, F, V = dims(spec)
+    out = []
+    if pp == 0:
+        out.append(("embed.word", V * H // TP))
+        if spec.max_pos:
+            out.append(("embed.pos", spec.max_pos * H))
+    per = spec.n_layers // PP
+    for l in range(pp * per, (pp + 1) * per):
+        out += layer_param_sizes(spec, TP, l)
+    if pp == PP - 1:
+        out.append(("final_norm.w", H))
+        if spec.norm_bias:
+            out.append(("final_norm.b", H))
+        if not spec.tied_embed:
+            out.append(("lm_head.w", V * H // TP))
+        elif PP > 1:
+            out.append(("embed.word(tied copy)", V * H // TP))
+    return out
+
+
+def n_local(spec, TP, PP, pp):
+    return sum(n for _, n in stage_param_sizes(spec, TP, PP, pp))
+
+
+def n_pad(spec, TP, PP, DP, pad_multiple, pp):
+    q = DP * pad_multiple
+    return (n_local(spec, TP, PP, pp) + q - 1) // q * q
+
+
+def owner(spec, TP, tp, phys, k):
+    """(names, idx): logical tensor name and row-major logical index of local
+    elements k (int64 array) of physical parameter `phys` on TP rank `tp`."""
+    H, hd, Q, KV, F, V = dims(spec)
+    k = np.asarray(k, np.int64)
+    base = phys.split("(")[0]
+    pre = base[:base.index(".") + 1] if base.startswith("L") else ""
+    leaf = base[len(pre):]
+    names = np.empty(k.shape, dtype=object)
+
+    if leaf in ("ln1.w", "ln1.b", "ln2.w", "ln2.b", "o.b", "down.b", "final_norm.w",
+                "final_norm.b", "embed.pos"):                    # replicated
+        names[:] = base
+        return names, k
+    if leaf in ("embed.word", "lm_head.w"):                      # column-parallel [V, H]
+        names[:] = base
+        return names, tp * (V // TP) * H + k
+    if leaf == "o.w":                                            # row-parallel [H, Q]
+        w = Q // TP
+        names[:] = base
+        return names, (k // w) * Q + tp * w + k % w
+    if leaf == "fc2.w":                                          # row-parallel [H, F]
+        w = F // TP
+        names[:] = pre + "down.w"
+        return names, (k // w) * F + tp * w + k % w
+    if leaf in ("qkv.w", "qkv.b"):
+        C = H if leaf == "qkv.w" else 1
+        sfx = leaf[-1]
+        qpg = spec.n_q_heads // spec.n_kv_heads
+        g_loc = spec.n_kv_heads // TP
+        i, j = k // C, k % C
+        G = (qpg + 2) * hd
+        g = tp * g_loc + i // G
+        w = i % G
+        is_q, is_k = w < qpg * hd, (w >= qpg * hd) & (w < (qpg + 1) * hd)
+        row = np.where(is_q, g * qpg * hd + w,
+                       np.where(is_k, g * hd + (w - qpg * hd), g * hd + (w - (qpg + 1) * hd)))
+        names[:] = pre + "v." + sfx
+        names[is_k] = pre + "k." + sfx
+        names[is_q] = pre + "q." + sfx
+        return names, row * C + j
+    if leaf in ("fc1.w", "fc1.b"):
+        C = H if leaf == "fc1.w" else 1
+        sfx = leaf[-1]
+        n = F // TP
+        i, j = k // C, k % C
+        if not spec.glu:
+            names[:] = pre + "up." + sfx
+            return names, (tp * n + i) * C + j
+        is_gate = i < n
+        row = np.where(is_gate, tp * n + i, tp * n + i - n)
+        names[:] = pre + "up." + sfx
+        names[is_gate] = pre + "gate." + sfx
+        return names, row * C + j
+    raise KeyError(phys)
+
+
+def column_ownership(spec, TP, PP, tp, pp):
+    """For flat offsets 0..N_local-1 of rank column (tp, pp): (names, idx, canonical).
+
+    canonical[k] is False where the element is a replica that a gather must not
+    read: TP-replicated parameters on tp > 0 and the tied-embedding copy."""
+    names, idx, canon = [], [], []
+    for phys, n in stage_param_sizes(spec, TP, PP, pp):
+        nm, ix = owner(spec, TP, tp, phys, np.arange(n, dtype=np.int64))
+        names.append(nm)
+        idx.append(ix)
+        leaf = phys.split(".", 1)[1] if phys.startswith("L") else phys
+        replicated = leaf in ("ln1.w", "ln1.b", "ln2.w", "ln2.b", "o.b", "down.b", "final_norm.w",
+                              "final_norm.b", "embed.pos")
+        ok = not (replicated and tp > 0) and "(tied copy)" not in phys
+        canon.append(np.full(n, ok))
+    return np.concatenate(names), np.concatenate(idx), np.concatenate(canon)

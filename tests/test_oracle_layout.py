@@ -1,0 +1,118 @@
+"""Pins the oracle's split and gather to the ownership formulas.
+
+A state whose every element equals its own logical index (and a second one whose
+every element equals the ordinal of its logical tensor) is split by the oracle;
+each element of each rank's buffer must then hold exactly what the closed-form
+ownership function of tests/ownership.py says that position owns."""
+import numpy as np
+import pytest
+
+import liver_synth as synth
+import oracle
+import ownership as own
+from util import cfg_objects, make_world, assert_same, corrupt_replicas
+
+SPECS = {
+    "tiny_gpt": oracle.ModelSpec(**synth.CONFIGS["tiny_gpt"]["spec"]),
+    "gqa_glu": oracle.ModelSpec(n_layers=4, hidden=64, n_q_heads=8, n_kv_heads=4, ffn=96, vocab=128,
+                                glu=True),
+    "gqa_glu_bias_untied": oracle.ModelSpec(n_layers=2, hidden=48, n_q_heads=6, n_kv_heads=2, ffn=40,
+                                            vocab=64, max_pos=16, glu=True, norm_bias=True,
+                                            linear_bias=True),
+    "mqa_tied": oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=4, n_kv_heads=1, ffn=64, vocab=32,
+                                 tied_embed=True),
+}
+LAYOUTS = [(1, 1, 1, 128), (2, 1, 2, 128), (1, 2, 2, 128), (2, 2, 3, 4), (4, 2, 1, 1), (2, 1, 3, 1)]
+
+
+def _cases():
+    for sname, spec in SPECS.items():
+        for (tp, pp, dp, pm) in LAYOUTS:
+            lay = oracle.Layout(tp, pp, dp, pm)
+            try:
+                oracle.check_supported(spec, lay)
+            except ValueError:
+                continue
+            yield pytest.param(spec, lay, id=f"{sname}-tp{tp}pp{pp}dp{dp}pm{pm}")
+
+
+def _tensor_ordinal_state(spec):
+    shapes = oracle.logical_tensors(spec)
+    st = {k: {} for k in oracle.KINDS}
+    for i, (n, s) in enumerate(shapes.items()):
+        for k in oracle.KINDS:
+            st[k][n] = np.full(s, i + 1, oracle.WORD[k])
+    return st
+
+
+@pytest.mark.parametrize("spec,lay", list(_cases()))
+def test_split_matches_ownership(spec, lay):
+    shapes = oracle.logical_tensors(spec)
+    ordinal = {n: i + 1 for i, n in enumerate(shapes)}
+    w_idx = make_world(spec, lay, synth.index_encoded_state(shapes, half=0), poison=False)
+    w_hi = make_world(spec, lay, synth.index_encoded_state(shapes, half=1), poison=False)
+    w_ord = make_world(spec, lay, _tensor_ordinal_state(spec), poison=False)
+    for pp in range(lay.pp):
+        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp)
+        S = npad // lay.dp
+        for tp in range(lay.tp):
+            names, idx, _ = own.column_ownership(spec, lay.tp, lay.pp, tp, pp)
+            nl = len(names)
+            exp_idx = np.zeros(npad, np.int64)
+            exp_idx[:nl] = idx
+            exp_ord = np.zeros(npad, np.int64)
+            exp_ord[:nl] = [ordinal[n] for n in names]
+            for dp in range(lay.dp):
+                r = lay.rank(tp, pp, dp)
+                assert np.array_equal(w_idx[(r, oracle.PARAM)], (exp_idx & 0xFFFF).astype(np.uint16))
+                assert np.array_equal(w_hi[(r, oracle.PARAM)], ((exp_idx >> 16) & 0xFFFF).astype(np.uint16))
+                assert np.array_equal(w_ord[(r, oracle.PARAM)], exp_ord.astype(np.uint16))
+                for k in (oracle.MASTER, oracle.ADAM_M, oracle.ADAM_V):
+                    assert w_idx[(r, k)].shape == (S,)
+                    assert np.array_equal(w_idx[(r, k)], exp_idx[dp * S:(dp + 1) * S].astype(np.uint32))
+                    assert np.array_equal(w_ord[(r, k)], exp_ord[dp * S:(dp + 1) * S].astype(np.uint32))
+
+
+@pytest.mark.parametrize("spec,lay", list(_cases()))
+def test_gather_inverts_split(spec, lay):
+    """gather(split(x)) == x, with NaN-poisoned padding (never read) and every
+    logical element gathered exactly once (the gather raises otherwise)."""
+    shapes = oracle.logical_tensors(spec)
+    state = synth.logical_state(shapes, synth.SEED_BASE, "uniform")
+    world = make_world(spec, lay, state, poison=True)
+    for k in oracle.KINDS:
+        back = oracle.gather_logical(spec, lay, k, oracle.dict_reader(world))
+        assert list(back) == list(shapes)
+        for n in shapes:
+            assert np.array_equal(back[n], state[k][n]), (k, n)
+
+
+def test_gather_reads_lowest_replica():
+    """Replicated values differ on purpose: the gather must take tp=0 / dp=0 /
+    the first-stage embedding."""
+    spec = SPECS["tiny_gpt"]
+    lay = oracle.Layout(2, 2, 2, 4)
+    shapes = oracle.logical_tensors(spec)
+    state = synth.logical_state(shapes, 7, "uniform")
+    world = make_world(spec, lay, state)
+    corrupt_replicas(spec, lay, world)
+    for k in oracle.KINDS:
+        back = oracle.gather_logical(spec, lay, k, oracle.dict_reader(world))
+        for n in shapes:
+            assert np.array_equal(back[n], state[k][n]), (k, n)
+
+
+def test_gather_detects_broken_tiling(monkeypatch):
+    """The exactly-once check of the gather fires if a view misses elements."""
+    spec = SPECS["mqa_tied"]
+    lay = oracle.Layout(1, 1, 1, 1)
+    world = make_world(spec, lay, synth.logical_state(oracle.logical_tensors(spec), 3, "uniform"))
+    real = oracle.reshard_oracle.stage_view
+
+    def broken(spec_, lay_, tp, pp):
+        sv = real(spec_, lay_, tp, pp)
+        sv.params[0].canonical = False          # nobody provides embed.word any more
+        return sv
+    monkeypatch.setattr(oracle.reshard_oracle, "stage_view", broken)
+    with pytest.raises(AssertionError):
+        oracle.gather_logical(spec, lay, oracle.MASTER, oracle.dict_reader(world))
