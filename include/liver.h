@@ -1,0 +1,203 @@
+/*
+ * liver.h -- C ABI of the MI355X (gfx950) online-resharding library.
+ *
+ * Online resharding of mixed-parallel training state, the data path of LiveR's
+ * live reconfiguration (LiveR, Section 4.6 "Streaming Resharding" and Appendix
+ * A.2): model weights (bf16), fp32 master weights and Adam m / v laid out for a
+ * source (TP, PP, DP) world are reshaped into a target (TP', PP', DP') world.
+ *
+ *   liver_plan_create   metadata-only planning (Section 4.6.1, Appendix A.2.2):
+ *                       every (source view, target view) pair of each logical
+ *                       tensor is intersected; non-empty intersections become
+ *                       copy descriptors (the paper's TransferTask), ordered
+ *                       layer-major and cut into a stream of fixed-size staging
+ *                       chunks (Section 4.6.2, Section 5: "fixed-size chunks").
+ *   liver_pack          source half of Algorithm 1 (slice <- T[p.bounds]): gather
+ *                       the pieces of one chunk from the source shards into the
+ *                       contiguous staging chunk (the wire format).
+ *   liver_unpack        target half of Algorithm 1 ("assemble received chunks"):
+ *                       scatter one staging chunk into the target shards, writing
+ *                       straight into the pre-allocated target storage (Appendix
+ *                       A.1); optionally re-derives bf16 weights from fp32.
+ *   liver_reshard       the same result in one pass, source shards -> target
+ *                       shards, no staging (single-GPU fused path).
+ *
+ * All logical ranks' buffers live in the memory of ONE GPU.  The library never
+ * allocates in pack / unpack / reshard, never synchronises the host with the
+ * device in them, and never writes a source buffer (the old world stays intact
+ * until the caller commits: Section 4.8 "Failure fallback").  Extra device
+ * memory is the caller's one staging chunk plus the plan's descriptor table
+ * (bounded-memory guarantee, Appendix A.1, Theorem 1).
+ *
+ * Physical layout conventions (the paper leaves them to the training framework;
+ * these are the Megatron-style ones this library implements):
+ *   - logical tensors are row-major [out_features, in_features];
+ *   - column-parallel linears (q/k/v, gate/up, embeddings, lm_head) are split in
+ *     contiguous row blocks over TP; row-parallel linears (o, down) in contiguous
+ *     column blocks; norms, position embeddings and biases of row-parallel
+ *     linears are replicated over TP;
+ *   - q, k, v are one fused parameter per rank, grouped per kv-head group:
+ *     [q rows of group g ; k rows of g ; v rows of g] for the rank's groups in
+ *     ascending order; gated FFNs store [gate rows of the rank ; up rows of the
+ *     rank] as one parameter;
+ *   - a (tp, pp) rank's parameters are flattened and packed back to back in
+ *     forward order (word/position embedding on the first stage; per layer ln1,
+ *     qkv, o, ln2, fc1, fc2 with each bias after its weight; final norm and
+ *     lm_head -- or a second copy of the tied word embedding if PP > 1 -- on the
+ *     last stage); stage pp holds layers [pp*L/PP, (pp+1)*L/PP);
+ *   - the flat buffer is zero-padded to N_pad, a multiple of DP*pad_multiple
+ *     elements.  LIVER_PARAM_BF16 holds all N_pad elements on every DP rank;
+ *     LIVER_MASTER_F32 / LIVER_ADAM_M_F32 / LIVER_ADAM_V_F32 are split evenly:
+ *     DP rank d holds elements [d*S, (d+1)*S), S = N_pad/DP (distributed
+ *     optimizer);
+ *   - a value that exists several times in the source world is read from the
+ *     copy with the lowest coordinate (dp = 0, tp = 0, first stage); source
+ *     padding is never read; target padding is written +0.
+ *
+ * Buffer tables: src_bufs[rank*4 + kind], dst_bufs[rank*4 + kind] are DEVICE
+ * pointers, rank = tp + TP*(dp + DP*pp).  Entries the plan does not use
+ * (liver_plan_buffer_used == 0) may be NULL.  The tables themselves are HOST
+ * arrays, read before the call returns.
+ *
+ * Every function returns LIVER_OK (0) or a negative LIVER_E_* code and writes
+ * nothing on error.  No exceptions cross this boundary.
+ */
+#ifndef LIVER_H
+#define LIVER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct liver_plan liver_plan_t; /* opaque, owned by the library */
+
+enum { LIVER_PARAM_BF16 = 0, LIVER_MASTER_F32 = 1, LIVER_ADAM_M_F32 = 2, LIVER_ADAM_V_F32 = 3,
+       LIVER_NUM_KINDS = 4 };
+
+/* liver_model_spec_t.flags */
+enum { LIVER_GLU = 1u,         /* gated FFN: gate.w + up.w (SwiGLU); else a plain 2-layer MLP */
+       LIVER_NORM_BIAS = 2u,   /* LayerNorm (weight + bias); else RMSNorm (weight only) */
+       LIVER_LINEAR_BIAS = 4u, /* every linear has a bias */
+       LIVER_TIED_EMBED = 8u   /* no lm_head; output projection reuses embed.word */ };
+
+/* liver_layout_t.flags (target layout only) */
+enum { LIVER_DERIVE_BF16 = 1u  /* target PARAM = round-to-nearest-even bf16 of the source MASTER
+                                  element with the same logical index; source PARAM is not read */ };
+
+enum { LIVER_OK = 0, LIVER_E_INVALID_ARG = -1, LIVER_E_UNSUPPORTED = -2, LIVER_E_NOMEM = -3,
+       LIVER_E_HIP = -4, LIVER_E_NO_DEVICE = -5 };
+
+typedef struct {
+    int32_t n_layers, hidden, n_q_heads, n_kv_heads, ffn, vocab;
+    int32_t max_pos;   /* rows of the learned position embedding; 0 = none */
+    uint32_t flags;    /* LIVER_GLU | LIVER_NORM_BIAS | LIVER_LINEAR_BIAS | LIVER_TIED_EMBED */
+} liver_model_spec_t;
+
+typedef struct {
+    int32_t tp, pp, dp;
+    int32_t pad_multiple;               /* flat buffers are padded to a multiple of dp*pad_multiple */
+    int32_t only_tp, only_pp, only_dp;  /* target layout: -1 = every rank, else plan only the share of
+                                           the ranks with this coordinate.  Source layout: must be -1 */
+    uint32_t flags;                     /* target layout: LIVER_DERIVE_BF16.  Source layout: 0 */
+    uint32_t kind_mask;                 /* target layout: bit k set = buffer kind k takes part;
+                                           0 = all four.  Source layout: 0 */
+} liver_layout_t;
+
+typedef struct {
+    int64_t n_chunks;            /* staging chunks in the stream = ceil(stream_bytes / chunk_bytes) */
+    int64_t n_desc;              /* descriptors of the direct path */
+    int64_t n_desc_pack, n_desc_unpack;
+    int64_t stream_bytes;        /* bytes on the wire, all chunks */
+    int64_t bytes_read;          /* source bytes the direct path reads */
+    int64_t bytes_written;       /* target bytes the direct path writes (incl. zero padding) */
+    int64_t pad_bytes;           /* of bytes_written: zero padding */
+    int64_t table_bytes_device;  /* the plan's only device allocation */
+    int32_t n_src_ranks, n_dst_ranks;
+    int32_t n_src_bufs_used, n_dst_bufs_used;
+} liver_plan_info_t;
+
+/* One copy descriptor, as the planner sees it (for inspection and tests).
+ * Offsets, strides and run are in ELEMENTS of the buffer they refer to; a rank of
+ * -1 means the staging chunk (whose elements have the size of the source kind's
+ * type and whose rows are packed tightly).  Row i of the piece is
+ * src[src_off + i*src_stride .. +run) -> dst[dst_off + i*dst_stride .. +run). */
+enum { LIVER_OP_COPY = 0, LIVER_OP_CAST_BF16 = 1, LIVER_OP_ZERO = 2 };
+enum { LIVER_LIST_DIRECT = 0, LIVER_LIST_PACK = 1, LIVER_LIST_UNPACK = 2 };
+typedef struct {
+    int32_t op;                  /* LIVER_OP_*; ZERO has no source */
+    int32_t chunk;               /* pack / unpack lists: chunk index; direct list: -1 */
+    int32_t slot;                /* stream order: 0 = embeddings, 1 + l = layer l, L + 1 = final norm / head */
+    int32_t src_rank, src_kind;  /* -1, -1: staging chunk (unpack) or none (ZERO) */
+    int32_t dst_rank, dst_kind;  /* -1, -1: staging chunk (pack) */
+    int32_t reserved;
+    int64_t src_off, src_stride;
+    int64_t dst_off, dst_stride;
+    int64_t rows, run;
+} liver_desc_t;
+
+/* Plan the reshard of `spec` from world `src` to world `dst` (Section 4.6.1;
+ * Algorithm 1, line 1).  Touches metadata only -- no tensor data, no data pointers.
+ * chunk_bytes: size of the caller's staging chunk, a multiple of 256, >= 256.
+ * If a HIP device is present the descriptor tables are uploaded to the current
+ * device (the plan's single device allocation, freed by liver_plan_destroy); if
+ * not, the plan is host-only: it can be inspected but pack / unpack / reshard
+ * return LIVER_E_NO_DEVICE.
+ * Errors: INVALID_ARG (null pointer, bad chunk_bytes, non-positive dimension),
+ * UNSUPPORTED (n_layers % pp, hidden % n_q_heads, n_q_heads % n_kv_heads,
+ * n_kv_heads % tp, ffn % tp or vocab % tp non-zero on either side; only_* out of
+ * range or set on the source layout), NOMEM, HIP. */
+int liver_plan_create(const liver_model_spec_t* spec, const liver_layout_t* src,
+                      const liver_layout_t* dst, size_t chunk_bytes, liver_plan_t** out);
+
+/* Free the plan and its device table.  NULL is allowed.  The caller must have
+ * synchronised every stream that still runs a kernel of this plan. */
+void liver_plan_destroy(liver_plan_t* plan);
+
+int liver_plan_info(const liver_plan_t* plan, liver_plan_info_t* out);
+
+/* Size in bytes of buffer (side: 0 = source world, 1 = target world; rank; kind). */
+int liver_plan_buffer_bytes(const liver_plan_t* plan, int side, int rank, int kind, size_t* out);
+
+/* 1 if any descriptor reads (side 0) / writes (side 1) that buffer, 0 if not,
+ * negative on a bad argument. */
+int liver_plan_buffer_used(const liver_plan_t* plan, int side, int rank, int kind);
+
+/* Number of descriptors in a list (LIVER_LIST_*), and the i-th of them. */
+int64_t liver_plan_desc_count(const liver_plan_t* plan, int list);
+int liver_plan_desc(const liver_plan_t* plan, int list, int64_t i, liver_desc_t* out);
+
+/* Launch shape of the copy kernels: grid_blocks workgroups of 256 threads
+ * (0 = 8 per compute unit); tile_order 0 = each workgroup walks one contiguous
+ * range of tiles, 1 = workgroups interleave tile by tile; cache_hints bit 0 =
+ * non-temporal loads, bit 1 = non-temporal stores.  Not thread-safe against
+ * concurrent launches of the same plan. */
+int liver_plan_set_launch(liver_plan_t* plan, int grid_blocks, int tile_order, int cache_hints);
+
+/* Algorithm 1, source side: gather chunk `chunk` (0 <= chunk < n_chunks) from the
+ * source shards into `staging` (device, >= chunk_bytes, 256 B aligned).
+ * Asynchronous on `hip_stream` (a hipStream_t; NULL = the default stream).
+ * Bytes of the chunk that carry no payload are left untouched. */
+int liver_pack(const liver_plan_t* plan, int chunk, const void* const* src_bufs, void* staging,
+               void* hip_stream);
+
+/* Algorithm 1, target side: scatter chunk `chunk` from `staging` into the target
+ * shards (with LIVER_DERIVE_BF16: also the fused fp32 -> bf16 cast into PARAM);
+ * writes the zero padding that belongs to the chunk.  Chunks are independent:
+ * any order, or any subset repeated, gives the same target bytes. */
+int liver_unpack(const liver_plan_t* plan, int chunk, const void* staging, void* const* dst_bufs,
+                 void* hip_stream);
+
+/* The whole reshard in one pass: source shards -> target shards, plus zero
+ * padding.  Equals pack + unpack over all chunks, bit for bit. */
+int liver_reshard(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs,
+                  void* hip_stream);
+
+const char* liver_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIVER_H */

@@ -1,0 +1,237 @@
+"""ctypes binding of the C ABI declared in include/liver.h.
+
+The functions keep the names of the C entry points.  Buffer tables are given as
+{(rank, kind): tensor-or-address} dictionaries (or a ready ctypes array) and are
+marshalled into the rank*4+kind pointer tables the library expects.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Dict, Optional, Tuple
+
+PARAM, MASTER, ADAM_M, ADAM_V = 0, 1, 2, 3
+LIST_DIRECT, LIST_PACK, LIST_UNPACK = 0, 1, 2
+OP_COPY, OP_CAST_BF16, OP_ZERO = 0, 1, 2
+_GLU, _NORM_BIAS, _LINEAR_BIAS, _TIED = 1, 2, 4, 8
+_DERIVE = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libliver.so")
+
+
+class LiverError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"liver error {code}: {msg}")
+        self.code = code
+
+
+class _Spec(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "ffn", "vocab", "max_pos")] \
+        + [("flags", C.c_uint32)]
+
+
+class _Layout(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("tp", "pp", "dp", "pad_multiple", "only_tp", "only_pp", "only_dp")] \
+        + [("flags", C.c_uint32), ("kind_mask", C.c_uint32)]
+
+
+class PlanInfo(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("n_chunks", "n_desc", "n_desc_pack", "n_desc_unpack", "stream_bytes",
+                                         "bytes_read", "bytes_written", "pad_bytes", "table_bytes_device")] \
+        + [(n, C.c_int32) for n in ("n_src_ranks", "n_dst_ranks", "n_src_bufs_used", "n_dst_bufs_used")]
+
+
+class Desc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("op", "chunk", "slot", "src_rank", "src_kind", "dst_rank", "dst_kind",
+                                         "reserved")] \
+        + [(n, C.c_int64) for n in ("src_off", "src_stride", "dst_off", "dst_stride", "rows", "run")]
+
+
+@dataclass(frozen=True)
+class ModelSpec:
+    n_layers: int
+    hidden: int
+    n_q_heads: int
+    n_kv_heads: int
+    ffn: int
+    vocab: int
+    max_pos: int = 0
+    glu: bool = False
+    norm_bias: bool = False
+    linear_bias: bool = False
+    tied_embed: bool = False
+
+    def _c(self) -> _Spec:
+        flags = (_GLU * self.glu) | (_NORM_BIAS * self.norm_bias) | (_LINEAR_BIAS * self.linear_bias) \
+            | (_TIED * self.tied_embed)
+        return _Spec(self.n_layers, self.hidden, self.n_q_heads, self.n_kv_heads, self.ffn, self.vocab,
+                     self.max_pos, flags)
+
+
+@dataclass(frozen=True)
+class Layout:
+    tp: int
+    pp: int
+    dp: int
+    pad_multiple: int = 128
+    only_tp: int = -1
+    only_pp: int = -1
+    only_dp: int = -1
+    derive_bf16: bool = False
+    kinds: Optional[Tuple[int, ...]] = None      # None = all four
+
+    @property
+    def n_ranks(self) -> int:
+        return self.tp * self.pp * self.dp
+
+    def rank(self, tp: int, pp: int, dp: int) -> int:
+        return tp + self.tp * (dp + self.dp * pp)
+
+    def _c(self) -> _Layout:
+        mask = 0 if self.kinds is None else sum(1 << k for k in set(self.kinds))
+        return _Layout(self.tp, self.pp, self.dp, self.pad_multiple, self.only_tp, self.only_pp, self.only_dp,
+                       _DERIVE * self.derive_bf16, mask)
+
+
+def _load() -> C.CDLL:
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it first (python -m paper_2605_22014_amd.build, or "
+                          f"__graft_entry__.build()); there is no fallback implementation")
+    lib = C.CDLL(path)
+    P = C.c_void_p
+    lib.liver_plan_create.argtypes = [C.POINTER(_Spec), C.POINTER(_Layout), C.POINTER(_Layout), C.c_size_t, C.POINTER(P)]
+    lib.liver_plan_destroy.argtypes = [P]
+    lib.liver_plan_destroy.restype = None
+    lib.liver_plan_info.argtypes = [P, C.POINTER(PlanInfo)]
+    lib.liver_plan_buffer_bytes.argtypes = [P, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
+    lib.liver_plan_buffer_used.argtypes = [P, C.c_int, C.c_int, C.c_int]
+    lib.liver_plan_desc_count.argtypes = [P, C.c_int]
+    lib.liver_plan_desc_count.restype = C.c_int64
+    lib.liver_plan_desc.argtypes = [P, C.c_int, C.c_int64, C.POINTER(Desc)]
+    lib.liver_plan_set_launch.argtypes = [P, C.c_int, C.c_int, C.c_int]
+    lib.liver_pack.argtypes = [P, C.c_int, C.POINTER(P), P, P]
+    lib.liver_unpack.argtypes = [P, C.c_int, P, C.POINTER(P), P]
+    lib.liver_reshard.argtypes = [P, C.POINTER(P), C.POINTER(P), P]
+    lib.liver_strerror.argtypes = [C.c_int]
+    lib.liver_strerror.restype = C.c_char_p
+    return lib
+
+
+_lib = _load()
+
+
+def liver_strerror(code: int) -> str:
+    return _lib.liver_strerror(code).decode()
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise LiverError(rc, liver_strerror(rc))
+
+
+class Plan:
+    """Owner of a liver_plan_t*; freed on liver_plan_destroy or garbage collection."""
+
+    def __init__(self, handle: int, src: Layout, dst: Layout, chunk_bytes: int):
+        self.handle, self.src, self.dst, self.chunk_bytes = handle, src, dst, chunk_bytes
+
+    def __del__(self):
+        liver_plan_destroy(self)
+
+
+def liver_plan_create(spec: ModelSpec, src: Layout, dst: Layout, chunk_bytes: int) -> Plan:
+    h = C.c_void_p()
+    cs, ca, cb = spec._c(), src._c(), dst._c()
+    _check(_lib.liver_plan_create(C.byref(cs), C.byref(ca), C.byref(cb), chunk_bytes, C.byref(h)))
+    return Plan(h.value, src, dst, chunk_bytes)
+
+
+def liver_plan_destroy(plan: Plan) -> None:
+    if getattr(plan, "handle", None):
+        _lib.liver_plan_destroy(plan.handle)
+        plan.handle = None
+
+
+def liver_plan_info(plan: Plan) -> PlanInfo:
+    info = PlanInfo()
+    _check(_lib.liver_plan_info(plan.handle, C.byref(info)))
+    return info
+
+
+def liver_plan_buffer_bytes(plan: Plan, side: int, rank: int, kind: int) -> int:
+    n = C.c_size_t()
+    _check(_lib.liver_plan_buffer_bytes(plan.handle, side, rank, kind, C.byref(n)))
+    return n.value
+
+
+def liver_plan_buffer_used(plan: Plan, side: int, rank: int, kind: int) -> bool:
+    rc = _lib.liver_plan_buffer_used(plan.handle, side, rank, kind)
+    if rc < 0:
+        _check(rc)
+    return bool(rc)
+
+
+def liver_plan_desc_count(plan: Plan, which: int) -> int:
+    n = _lib.liver_plan_desc_count(plan.handle, which)
+    if n < 0:
+        _check(int(n))
+    return int(n)
+
+
+def liver_plan_desc(plan: Plan, which: int, i: int) -> Desc:
+    d = Desc()
+    _check(_lib.liver_plan_desc(plan.handle, which, i, C.byref(d)))
+    return d
+
+
+def liver_plan_set_launch(plan: Plan, grid_blocks: int = 0, tile_order: int = 0, cache_hints: int = 0) -> None:
+    _check(_lib.liver_plan_set_launch(plan.handle, grid_blocks, tile_order, cache_hints))
+
+
+def _addr(x) -> int:
+    if x is None:
+        return 0
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()          # torch tensor (device memory)
+
+
+def _table(bufs, n_ranks: int):
+    """{(rank, kind): tensor | address} -> void*[n_ranks*4]."""
+    if not isinstance(bufs, dict):
+        return bufs               # already a ctypes array
+    arr = (C.c_void_p * (n_ranks * 4))()
+    for (rank, kind), t in bufs.items():
+        arr[rank * 4 + kind] = _addr(t)
+    return arr
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def liver_pack(plan: Plan, chunk: int, src_bufs, staging, stream=None) -> None:
+    _check(_lib.liver_pack(plan.handle, chunk, _table(src_bufs, plan.src.n_ranks), _addr(staging), _stream(stream)))
+
+
+def liver_unpack(plan: Plan, chunk: int, staging, dst_bufs, stream=None) -> None:
+    _check(_lib.liver_unpack(plan.handle, chunk, _addr(staging), _table(dst_bufs, plan.dst.n_ranks), _stream(stream)))
+
+
+def liver_reshard(plan: Plan, src_bufs, dst_bufs, stream=None) -> None:
+    _check(_lib.liver_reshard(plan.handle, _table(src_bufs, plan.src.n_ranks), _table(dst_bufs, plan.dst.n_ranks),
+                              _stream(stream)))
+
+
+def make_table(bufs: Dict[Tuple[int, int], object], n_ranks: int):
+    """Marshal a buffer dictionary once, for repeated calls."""
+    return _table(bufs, n_ranks)

@@ -1,0 +1,198 @@
+// The C ABI: plan lifetime, inspection, and the three data calls.
+#include <hip/hip_runtime_api.h>
+
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "launch.hpp"
+#include "plan.hpp"
+
+namespace {
+
+thread_local std::string g_last_detail;
+
+int fail(int code, const std::string& detail) {
+    g_last_detail = detail;
+    return code;
+}
+
+int n_ranks(const liver_layout_t& l) { return l.tp * l.pp * l.dp; }
+
+// Resolve the buffers of passes [p0, p1) of `list` and launch them in order.
+// Everything is validated before the first launch, so an error writes nothing.
+int run_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uint32_t p1, const void* const* src_bufs,
+               void* const* dst_bufs, const void* staging, void* hip_stream) {
+    if (plan->device < 0) return fail(LIVER_E_NO_DEVICE, "plan was created without a HIP device");
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess || cur != plan->device)
+        return fail(LIVER_E_INVALID_ARG, "current HIP device is not the one the plan was created on");
+    for (uint32_t p = p0; p < p1; ++p)
+        for (const liver::BufRef& r : list.passes[p].bufs) {
+            const void* ptr = r.side == 0   ? (src_bufs ? src_bufs[(size_t)r.rank * 4 + r.kind] : nullptr)
+                              : r.side == 1 ? (dst_bufs ? dst_bufs[(size_t)r.rank * 4 + r.kind] : nullptr)
+                                            : staging;
+            if (!ptr) return fail(LIVER_E_INVALID_ARG, "a buffer the plan uses is NULL");
+            if ((uintptr_t)ptr % 16) return fail(LIVER_E_INVALID_ARG, "buffers must be 16-byte aligned");
+        }
+    const uint32_t max_grid = plan->grid_blocks > 0 ? (uint32_t)plan->grid_blocks : (uint32_t)plan->n_cu * 8u;
+    for (uint32_t p = p0; p < p1; ++p) {
+        const liver::Pass& pass = list.passes[p];
+        if (pass.n_tiles == 0) continue;
+        liver::PassArgs args;
+        args.descs = (const liver::DevDesc*)((const char*)plan->dev_table + list.dev_offset) + pass.desc_begin;
+        args.n_desc = pass.desc_count;
+        args.n_tiles = pass.n_tiles;
+        args.tile_order = (uint32_t)plan->tile_order;
+        args.reserved = 0;
+        size_t i = 0;
+        for (const liver::BufRef& r : pass.bufs) {
+            const void* ptr = r.side == 0 ? src_bufs[(size_t)r.rank * 4 + r.kind]
+                              : r.side == 1 ? dst_bufs[(size_t)r.rank * 4 + r.kind] : staging;
+            args.bufs[i++] = (char*)ptr;
+        }
+        for (; i < (size_t)liver::MAX_PASS_BUFS; ++i) args.bufs[i] = nullptr;
+        const uint32_t grid = pass.n_tiles < max_grid ? pass.n_tiles : max_grid;
+        hipError_t e = liver::launch_pass(args, grid, plan->cache_hints, (hipStream_t)hip_stream);
+        if (e != hipSuccess) return fail(LIVER_E_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
+    }
+    return LIVER_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int liver_plan_create(const liver_model_spec_t* spec, const liver_layout_t* src, const liver_layout_t* dst,
+                      size_t chunk_bytes, liver_plan_t** out) {
+    if (!spec || !src || !dst || !out) return fail(LIVER_E_INVALID_ARG, "null argument");
+    liver_plan* plan = nullptr;
+    try {
+        plan = new liver_plan;
+        plan->spec = *spec, plan->src = *src, plan->dst = *dst, plan->chunk_bytes = chunk_bytes;
+        std::string why;
+        int rc = liver::build_plan(*plan, why);
+        if (rc != LIVER_OK) {
+            delete plan;
+            return fail(rc, why);
+        }
+    } catch (const std::bad_alloc&) {
+        delete plan;
+        return fail(LIVER_E_NOMEM, "host allocation failed");
+    }
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) == hipSuccess && n_dev > 0) {
+        int dev = 0, cu = 0;
+        void* table = nullptr;
+        const size_t bytes = (size_t)plan->info.table_bytes_device;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess && bytes) e = hipMalloc(&table, bytes);
+        for (const liver::List* l : {&plan->direct, &plan->pack, &plan->unpack})
+            if (e == hipSuccess && !l->dev.empty())
+                e = hipMemcpy((char*)table + l->dev_offset, l->dev.data(), l->dev.size() * sizeof(liver::DevDesc),
+                              hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            if (table) (void)hipFree(table);
+            const int code = e == hipErrorOutOfMemory ? LIVER_E_NOMEM : LIVER_E_HIP;
+            delete plan;
+            return fail(code, std::string("descriptor table upload: ") + hipGetErrorString(e));
+        }
+        plan->dev_table = table, plan->device = dev, plan->n_cu = cu > 0 ? cu : 256;
+    } else {
+        (void)hipGetLastError();  // no device: host-only plan
+    }
+    *out = plan;
+    return LIVER_OK;
+}
+
+void liver_plan_destroy(liver_plan_t* plan) {
+    if (!plan) return;
+    if (plan->dev_table) (void)hipFree(plan->dev_table);
+    delete plan;
+}
+
+int liver_plan_info(const liver_plan_t* plan, liver_plan_info_t* out) {
+    if (!plan || !out) return fail(LIVER_E_INVALID_ARG, "null argument");
+    *out = plan->info;
+    return LIVER_OK;
+}
+
+int liver_plan_buffer_bytes(const liver_plan_t* plan, int side, int rank, int kind, size_t* out) {
+    if (!plan || !out || side < 0 || side > 1 || kind < 0 || kind >= LIVER_NUM_KINDS)
+        return fail(LIVER_E_INVALID_ARG, "bad argument");
+    const liver_layout_t& lay = side ? plan->dst : plan->src;
+    if (rank < 0 || rank >= n_ranks(lay)) return fail(LIVER_E_INVALID_ARG, "rank out of range");
+    const int pp = rank / (lay.tp * lay.dp);
+    const liver::StageSize& st = (side ? plan->dst_stage : plan->src_stage)[pp];
+    *out = kind == LIVER_PARAM_BF16 ? (size_t)st.n_pad * 2 : (size_t)st.S * 4;
+    return LIVER_OK;
+}
+
+int liver_plan_buffer_used(const liver_plan_t* plan, int side, int rank, int kind) {
+    if (!plan || side < 0 || side > 1 || kind < 0 || kind >= LIVER_NUM_KINDS)
+        return fail(LIVER_E_INVALID_ARG, "bad argument");
+    if (rank < 0 || rank >= n_ranks(side ? plan->dst : plan->src)) return fail(LIVER_E_INVALID_ARG, "rank out of range");
+    return plan->used[side][(size_t)rank * 4 + kind];
+}
+
+int64_t liver_plan_desc_count(const liver_plan_t* plan, int list) {
+    if (!plan || list < 0 || list > 2) return fail(LIVER_E_INVALID_ARG, "bad argument");
+    const liver::List& l = list == LIVER_LIST_DIRECT ? plan->direct : list == LIVER_LIST_PACK ? plan->pack : plan->unpack;
+    return (int64_t)l.pub.size();
+}
+
+int liver_plan_desc(const liver_plan_t* plan, int list, int64_t i, liver_desc_t* out) {
+    if (!plan || !out || list < 0 || list > 2) return fail(LIVER_E_INVALID_ARG, "bad argument");
+    const liver::List& l = list == LIVER_LIST_DIRECT ? plan->direct : list == LIVER_LIST_PACK ? plan->pack : plan->unpack;
+    if (i < 0 || i >= (int64_t)l.pub.size()) return fail(LIVER_E_INVALID_ARG, "descriptor index out of range");
+    *out = l.pub[(size_t)i];
+    return LIVER_OK;
+}
+
+int liver_plan_set_launch(liver_plan_t* plan, int grid_blocks, int tile_order, int cache_hints) {
+    if (!plan || grid_blocks < 0 || grid_blocks > 65536 || tile_order < 0 || tile_order > 1 || cache_hints < 0 ||
+        cache_hints > 3)
+        return fail(LIVER_E_INVALID_ARG, "bad launch shape");
+    plan->grid_blocks = grid_blocks, plan->tile_order = tile_order, plan->cache_hints = cache_hints;
+    return LIVER_OK;
+}
+
+int liver_pack(const liver_plan_t* plan, int chunk, const void* const* src_bufs, void* staging, void* hip_stream) {
+    if (!plan || !src_bufs || !staging) return fail(LIVER_E_INVALID_ARG, "null argument");
+    if (chunk < 0 || chunk >= plan->info.n_chunks) return fail(LIVER_E_INVALID_ARG, "chunk index out of range");
+    if ((uintptr_t)staging % 256) return fail(LIVER_E_INVALID_ARG, "staging must be 256-byte aligned");
+    return run_passes(plan, plan->pack, plan->pack.chunk_pass[chunk], plan->pack.chunk_pass[chunk + 1], src_bufs, nullptr,
+                      staging, hip_stream);
+}
+
+int liver_unpack(const liver_plan_t* plan, int chunk, const void* staging, void* const* dst_bufs, void* hip_stream) {
+    if (!plan || !dst_bufs || !staging) return fail(LIVER_E_INVALID_ARG, "null argument");
+    if (chunk < 0 || chunk >= plan->info.n_chunks) return fail(LIVER_E_INVALID_ARG, "chunk index out of range");
+    if ((uintptr_t)staging % 256) return fail(LIVER_E_INVALID_ARG, "staging must be 256-byte aligned");
+    return run_passes(plan, plan->unpack, plan->unpack.chunk_pass[chunk], plan->unpack.chunk_pass[chunk + 1], nullptr,
+                      dst_bufs, staging, hip_stream);
+}
+
+int liver_reshard(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs, void* hip_stream) {
+    if (!plan || !src_bufs || !dst_bufs) return fail(LIVER_E_INVALID_ARG, "null argument");
+    return run_passes(plan, plan->direct, 0, (uint32_t)plan->direct.passes.size(), src_bufs, dst_bufs, nullptr, hip_stream);
+}
+
+const char* liver_strerror(int code) {
+    static thread_local std::string msg;
+    const char* base = "unknown error";
+    switch (code) {
+        case LIVER_OK: return "ok";
+        case LIVER_E_INVALID_ARG: base = "invalid argument"; break;
+        case LIVER_E_UNSUPPORTED: base = "unsupported configuration"; break;
+        case LIVER_E_NOMEM: base = "out of memory"; break;
+        case LIVER_E_HIP: base = "HIP error"; break;
+        case LIVER_E_NO_DEVICE: base = "no HIP device"; break;
+    }
+    msg = base;
+    if (!g_last_detail.empty()) msg += ": " + g_last_detail;
+    return msg.c_str();
+}
+
+}  // extern "C"

@@ -1,0 +1,24 @@
+// Launch interface between the C ABI (host) and the kernels.
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include "plan.hpp"
+
+namespace liver {
+
+// Arguments of one launch, passed by value (kernarg segment, < 4 KiB): the
+// descriptor range in the plan's device table and the resolved buffer pointers.
+struct PassArgs {
+    const DevDesc* descs;
+    uint32_t n_desc;
+    uint32_t n_tiles;
+    uint32_t tile_order;
+    uint32_t reserved;
+    char* bufs[MAX_PASS_BUFS];
+};
+static_assert(sizeof(PassArgs) <= 3584, "kernel arguments must fit the kernarg segment");
+
+// Enqueue one pass on `stream` with `grid` workgroups (1 <= grid <= n_tiles).
+hipError_t launch_pass(const PassArgs& args, uint32_t grid, int cache_hints, hipStream_t stream);
+
+}  // namespace liver

@@ -1,0 +1,627 @@
+// Host planner: views -> intersections -> copy descriptors -> chunked stream.
+//
+// LiveR, Section 4.6.1 and Appendix A.2.2: the state is a set of logical tensors;
+// each rank's view of a tensor is a set of index rectangles; for every (source
+// view, target view) pair of a tensor the non-empty intersection becomes a
+// transfer task with exact slice bounds.  Only metadata is touched.  The paper's
+// view is a single hyper-rectangle; fused QKV, gated FFNs and a DP slice of a
+// flattened shard need a LIST of rectangles per rank, each with its offset in
+// the rank's flat buffer -- that is the only generalisation made here.
+//
+// Section 4.6.2 / Section 5 / Algorithm 1: tasks are executed layer by layer
+// through a fixed-size staging buffer.  Here the tasks are sorted layer-major,
+// laid out back to back on a byte stream and the stream is cut every chunk_bytes
+// (a task that straddles a cut is split at an element boundary).
+#include <algorithm>
+#include <cstring>
+#include <string>
+
+#include "plan.hpp"
+
+namespace liver {
+namespace {
+
+using i64 = int64_t;
+
+struct Geo {
+    i64 L, H, hd, nq, nkv, qpg, Q, KV, F, V, P;
+    bool glu, norm_bias, lin_bias, tied;
+};
+
+// logical tensor ids
+enum { T_EMBED_WORD = 0, T_EMBED_POS, T_FINAL_W, T_FINAL_B, T_LM_HEAD, T_GLOBALS };
+enum { LN1_W = 0, LN1_B, Q_W, K_W, V_W, Q_B, K_B, V_B, O_W, O_B, LN2_W, LN2_B, GATE_W, UP_W, GATE_B, UP_B,
+       DOWN_W, DOWN_B, T_PER_LAYER };
+
+// A rectangle of logical tensor `tensor` held densely (row-major, row length
+// c1-c0) at element offset `loff` of a rank column's flat buffer.
+struct Rect {
+    int32_t tensor, slot;
+    i64 r0, r1, c0, c1, loff;
+    bool canonical;  // may a gather read this copy?
+};
+
+struct Column {
+    int tp = 0, pp = 0;
+    std::vector<Rect> rects;
+    i64 n_local = 0;
+    int last_slot = 0;
+};
+
+// Physical parameter order and shapes of rank column (tp, pp).
+Column build_column(const Geo& g, int TP, int PP, int tp, int pp) {
+    Column col;
+    col.tp = tp;
+    col.pp = pp;
+    i64 off = 0;
+    auto add = [&](int tensor, int slot, i64 r0, i64 r1, i64 c0, i64 c1, bool canonical) {
+        col.rects.push_back({tensor, slot, r0, r1, c0, c1, off, canonical});
+        off += (r1 - r0) * (c1 - c0);
+        col.last_slot = slot;
+    };
+    const bool lead = (tp == 0);  // TP-replicated parameters are read from tp 0
+    const i64 g_loc = g.nkv / TP, fn = g.F / TP, qn = g.Q / TP, vn = g.V / TP;
+    if (pp == 0) {
+        add(T_EMBED_WORD, 0, tp * vn, (tp + 1) * vn, 0, g.H, true);
+        if (g.P) add(T_EMBED_POS, 0, 0, g.P, 0, g.H, lead);
+    }
+    const i64 per = g.L / PP;
+    for (i64 l = pp * per; l < (pp + 1) * per; ++l) {
+        const int slot = 1 + (int)l;
+        const int b = T_GLOBALS + (int)l * T_PER_LAYER;
+        add(b + LN1_W, slot, 0, 1, 0, g.H, lead);
+        if (g.norm_bias) add(b + LN1_B, slot, 0, 1, 0, g.H, lead);
+        for (i64 j = 0; j < g_loc; ++j) {  // fused qkv weight: [q of group ; k ; v] per kv group
+            const i64 gi = tp * g_loc + j;
+            add(b + Q_W, slot, gi * g.qpg * g.hd, (gi + 1) * g.qpg * g.hd, 0, g.H, true);
+            add(b + K_W, slot, gi * g.hd, (gi + 1) * g.hd, 0, g.H, true);
+            add(b + V_W, slot, gi * g.hd, (gi + 1) * g.hd, 0, g.H, true);
+        }
+        if (g.lin_bias)
+            for (i64 j = 0; j < g_loc; ++j) {
+                const i64 gi = tp * g_loc + j;
+                add(b + Q_B, slot, 0, 1, gi * g.qpg * g.hd, (gi + 1) * g.qpg * g.hd, true);
+                add(b + K_B, slot, 0, 1, gi * g.hd, (gi + 1) * g.hd, true);
+                add(b + V_B, slot, 0, 1, gi * g.hd, (gi + 1) * g.hd, true);
+            }
+        add(b + O_W, slot, 0, g.H, tp * qn, (tp + 1) * qn, true);  // row-parallel: a strip of every row
+        if (g.lin_bias) add(b + O_B, slot, 0, 1, 0, g.H, lead);
+        add(b + LN2_W, slot, 0, 1, 0, g.H, lead);
+        if (g.norm_bias) add(b + LN2_B, slot, 0, 1, 0, g.H, lead);
+        if (g.glu) add(b + GATE_W, slot, tp * fn, (tp + 1) * fn, 0, g.H, true);
+        add(b + UP_W, slot, tp * fn, (tp + 1) * fn, 0, g.H, true);
+        if (g.lin_bias) {
+            if (g.glu) add(b + GATE_B, slot, 0, 1, tp * fn, (tp + 1) * fn, true);
+            add(b + UP_B, slot, 0, 1, tp * fn, (tp + 1) * fn, true);
+        }
+        add(b + DOWN_W, slot, 0, g.H, tp * fn, (tp + 1) * fn, true);
+        if (g.lin_bias) add(b + DOWN_B, slot, 0, 1, 0, g.H, lead);
+    }
+    if (pp == PP - 1) {
+        const int slot = (int)g.L + 1;
+        add(T_FINAL_W, slot, 0, 1, 0, g.H, lead);
+        if (g.norm_bias) add(T_FINAL_B, slot, 0, 1, 0, g.H, lead);
+        if (!g.tied)
+            add(T_LM_HEAD, slot, tp * vn, (tp + 1) * vn, 0, g.H, true);
+        else if (PP > 1)  // second copy of the tied embedding: written, never read
+            add(T_EMBED_WORD, slot, tp * vn, (tp + 1) * vn, 0, g.H, false);
+    }
+    col.n_local = off;
+    return col;
+}
+
+// A strided 2-D piece with one source and one or more destinations.  Offsets and
+// strides in elements; row i is [off + i*stride, off + i*stride + run).
+struct Dst {
+    int32_t rank, kind, op;
+    i64 off, stride;
+};
+struct Entry {
+    int32_t slot = 0, src_rank = -1, src_kind = -1;
+    i64 src_off = 0, src_stride = 0, rows = 1, run = 0;
+    std::vector<Dst> dsts;
+};
+
+inline int elem_bytes(int kind) { return kind == LIVER_PARAM_BF16 ? 2 : 4; }
+
+// Payload elements [p0, p1) of `e` (row-major over rows x run) as up to three
+// pieces: the tail of a row, whole rows, the head of a row.
+void slice(const Entry& e, i64 p0, i64 p1, std::vector<Entry>& out) {
+    auto sub = [&](i64 row, i64 col, i64 nrows, i64 ncols) {
+        Entry s = e;
+        s.src_off = e.src_off + row * e.src_stride + col;
+        s.rows = nrows;
+        s.run = ncols;
+        bool dense = (e.src_rank < 0 || e.src_stride == ncols);
+        for (auto& d : s.dsts) {
+            d.off += row * d.stride + col;
+            dense = dense && d.stride == ncols;
+        }
+        if (nrows == 1 || dense) {  // one contiguous run on every side
+            s.run = nrows * ncols;
+            s.rows = 1;
+            s.src_stride = s.run;
+            for (auto& d : s.dsts) d.stride = s.run;
+        }
+        out.push_back(std::move(s));
+    };
+    if (p0 >= p1) return;
+    if (e.rows == 1) {
+        sub(0, p0, 1, p1 - p0);
+        return;
+    }
+    i64 r0 = p0 / e.run, c0 = p0 % e.run, r1 = p1 / e.run, c1 = p1 % e.run;
+    if (r0 == r1) {
+        sub(r0, c0, 1, c1 - c0);
+        return;
+    }
+    if (c0 > 0) {
+        sub(r0, c0, 1, e.run - c0);
+        ++r0;
+    }
+    if (r1 > r0) sub(r0, 0, r1 - r0, e.run);
+    if (c1 > 0) sub(r1, 0, 1, c1);
+}
+
+// Payload positions at which the piece (off, stride, rows, run) crosses a
+// multiple of S in flat-buffer coordinates.
+void boundary_cuts(i64 off, i64 stride, i64 rows, i64 run, i64 S, std::vector<i64>& cuts) {
+    const i64 end = off + (rows - 1) * stride + run;  // one past the last element
+    for (i64 b = (off / S + 1) * S; b < end; b += S) {
+        if (rows == 1) {
+            cuts.push_back(b - off);
+            continue;
+        }
+        const i64 x = b - off - run;                  // rows i with off+i*stride+run <= b lie before b
+        const i64 i = x < 0 ? 0 : x / stride + 1;     // first row that reaches past b
+        if (i >= rows) continue;
+        const i64 start = off + i * stride;
+        cuts.push_back(start >= b ? i * run : i * run + (b - start));
+    }
+}
+
+struct Builder {
+    liver_plan& plan;
+    Geo g{};
+    std::vector<Entry> entries;
+    std::string why;
+
+    explicit Builder(liver_plan& p) : plan(p) {}
+
+    int rank_of(const liver_layout_t& lay, int tp, int pp, int dp) const { return tp + lay.tp * (dp + lay.dp * pp); }
+    bool dst_dp_planned(int dp) const { return plan.dst.only_dp < 0 || plan.dst.only_dp == dp; }
+    bool kind_on(int k) const { return plan.dst.kind_mask == 0 || ((plan.dst.kind_mask >> k) & 1u); }
+
+    void push_bounded(Entry&& e) {  // keep every entry below 2^30 elements (32-bit unit counters)
+        const i64 lim = i64(1) << 30, total = e.rows * e.run;
+        if (total <= lim) {
+            entries.push_back(std::move(e));
+            return;
+        }
+        for (i64 p = 0; p < total; p += lim) slice(e, p, std::min(total, p + lim), entries);
+    }
+
+    // One intersection piece in flat coordinates of columns (s_tp,s_pp) -> (d_tp,d_pp):
+    // expand it per buffer kind, clipping the fp32 kinds at the DP slice boundaries.
+    void expand(int slot, int s_tp, int s_pp, int d_tp, int d_pp, i64 s_off, i64 s_stride, i64 d_off,
+                i64 d_stride, i64 rows, i64 run) {
+        const liver_layout_t &S = plan.src, &D = plan.dst;
+        const bool derive = (D.flags & LIVER_DERIVE_BF16) != 0;
+        if (kind_on(LIVER_PARAM_BF16) && !derive) {
+            for (int dp = 0; dp < D.dp; ++dp) {
+                if (!dst_dp_planned(dp)) continue;
+                Entry e;
+                e.slot = slot;
+                e.src_rank = rank_of(S, s_tp, s_pp, 0);  // replicas are identical: read dp 0
+                e.src_kind = LIVER_PARAM_BF16;
+                e.src_off = s_off, e.src_stride = s_stride, e.rows = rows, e.run = run;
+                e.dsts.push_back({rank_of(D, d_tp, d_pp, dp), LIVER_PARAM_BF16, LIVER_OP_COPY, d_off, d_stride});
+                push_bounded(std::move(e));
+            }
+        }
+        const bool any_f32 = kind_on(LIVER_MASTER_F32) || kind_on(LIVER_ADAM_M_F32) || kind_on(LIVER_ADAM_V_F32);
+        if (!any_f32 && !(derive && kind_on(LIVER_PARAM_BF16))) return;
+        // cut at source and target DP slice boundaries
+        const i64 Ss = plan.src_stage[s_pp].S, Sd = plan.dst_stage[d_pp].S;
+        std::vector<i64> cuts{0, rows * run};
+        boundary_cuts(s_off, s_stride, rows, run, Ss, cuts);
+        boundary_cuts(d_off, d_stride, rows, run, Sd, cuts);
+        std::sort(cuts.begin(), cuts.end());
+        cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
+        Entry flat;
+        flat.slot = slot;
+        flat.src_rank = 0;
+        flat.src_off = s_off, flat.src_stride = s_stride, flat.rows = rows, flat.run = run;
+        flat.dsts.push_back({0, 0, LIVER_OP_COPY, d_off, d_stride});
+        std::vector<Entry> parts;
+        for (size_t c = 0; c + 1 < cuts.size(); ++c) slice(flat, cuts[c], cuts[c + 1], parts);
+        for (const Entry& p : parts) {
+            const int sdp = int(p.src_off / Ss), ddp = int(p.dsts[0].off / Sd);
+            const i64 s_local = p.src_off - sdp * Ss, d_local = p.dsts[0].off - ddp * Sd;
+            for (int k = LIVER_MASTER_F32; k <= LIVER_ADAM_V_F32; ++k) {
+                Entry e;
+                e.slot = slot;
+                e.src_rank = rank_of(S, s_tp, s_pp, sdp);
+                e.src_kind = k;
+                e.src_off = s_local, e.src_stride = p.src_stride, e.rows = p.rows, e.run = p.run;
+                if (kind_on(k) && dst_dp_planned(ddp))
+                    e.dsts.push_back({rank_of(D, d_tp, d_pp, ddp), k, LIVER_OP_COPY, d_local, p.dsts[0].stride});
+                if (k == LIVER_MASTER_F32 && derive && kind_on(LIVER_PARAM_BF16))
+                    for (int dp = 0; dp < D.dp; ++dp)  // PARAM replicas come from the MASTER element
+                        if (dst_dp_planned(dp))        // with the same logical index
+                            e.dsts.push_back({rank_of(D, d_tp, d_pp, dp), LIVER_PARAM_BF16, LIVER_OP_CAST_BF16,
+                                              p.dsts[0].off, p.dsts[0].stride});
+                if (!e.dsts.empty()) push_bounded(std::move(e));
+            }
+        }
+    }
+
+    void zero_padding(const Column& col) {
+        const liver_layout_t& D = plan.dst;
+        const StageSize& st = plan.dst_stage[col.pp];
+        if (st.n_pad == st.n_local) return;
+        for (int dp = 0; dp < D.dp; ++dp) {
+            if (!dst_dp_planned(dp)) continue;
+            const int rank = rank_of(D, col.tp, col.pp, dp);
+            for (int k = 0; k < LIVER_NUM_KINDS; ++k) {
+                if (!kind_on(k)) continue;
+                i64 lo = st.n_local, hi = st.n_pad, base = 0;
+                if (k != LIVER_PARAM_BF16) {
+                    base = dp * st.S;
+                    lo = std::max(lo, base);
+                    hi = std::min(hi, base + st.S);
+                }
+                if (lo >= hi) continue;
+                Entry e;
+                e.slot = col.last_slot;
+                e.run = hi - lo;
+                e.dsts.push_back({rank, k, LIVER_OP_ZERO, lo - base, hi - lo});
+                push_bounded(std::move(e));
+            }
+        }
+    }
+
+    int run();
+    void emit_lists();
+    int lower(List& list, bool staged);
+};
+
+int Builder::run() {
+    const liver_model_spec_t& sp = plan.spec;
+    const liver_layout_t &S = plan.src, &D = plan.dst;
+    if (sp.n_layers <= 0 || sp.hidden <= 0 || sp.n_q_heads <= 0 || sp.n_kv_heads <= 0 || sp.ffn <= 0 ||
+        sp.vocab <= 0 || sp.max_pos < 0 || (sp.flags & ~15u)) {
+        why = "model_spec: dimensions must be positive";
+        return LIVER_E_INVALID_ARG;
+    }
+    for (const liver_layout_t* l : {&S, &D})
+        if (l->tp <= 0 || l->pp <= 0 || l->dp <= 0 || l->pad_multiple <= 0) {
+            why = "layout: tp, pp, dp, pad_multiple must be positive";
+            return LIVER_E_INVALID_ARG;
+        }
+    if (plan.chunk_bytes < 256 || plan.chunk_bytes % 256) {
+        why = "chunk_bytes must be a positive multiple of 256";
+        return LIVER_E_INVALID_ARG;
+    }
+    if (sp.hidden % sp.n_q_heads || sp.n_q_heads % sp.n_kv_heads) {
+        why = "hidden % n_q_heads or n_q_heads % n_kv_heads != 0";
+        return LIVER_E_UNSUPPORTED;
+    }
+    for (const liver_layout_t* l : {&S, &D})
+        if (sp.n_layers % l->pp || sp.n_kv_heads % l->tp || sp.ffn % l->tp || sp.vocab % l->tp) {
+            why = "n_layers % pp, n_kv_heads % tp, ffn % tp or vocab % tp != 0";
+            return LIVER_E_UNSUPPORTED;
+        }
+    if (S.only_tp != -1 || S.only_pp != -1 || S.only_dp != -1 || S.flags || S.kind_mask) {
+        why = "source layout: only_* must be -1, flags and kind_mask 0";
+        return LIVER_E_UNSUPPORTED;
+    }
+    if (D.only_tp < -1 || D.only_tp >= D.tp || D.only_pp < -1 || D.only_pp >= D.pp || D.only_dp < -1 ||
+        D.only_dp >= D.dp || (D.flags & ~1u) || (D.kind_mask & ~15u)) {
+        why = "target layout: only_* out of range or unknown flag";
+        return LIVER_E_UNSUPPORTED;
+    }
+    if ((i64)S.tp * S.pp * S.dp > (i64(1) << 24) || (i64)D.tp * D.pp * D.dp > (i64(1) << 24)) {
+        why = "more than 2^24 ranks";
+        return LIVER_E_UNSUPPORTED;
+    }
+    g.L = sp.n_layers, g.H = sp.hidden, g.nq = sp.n_q_heads, g.nkv = sp.n_kv_heads;
+    g.hd = g.H / g.nq, g.qpg = g.nq / g.nkv, g.Q = g.nq * g.hd, g.KV = g.nkv * g.hd;
+    g.F = sp.ffn, g.V = sp.vocab, g.P = sp.max_pos;
+    g.glu = sp.flags & LIVER_GLU, g.norm_bias = sp.flags & LIVER_NORM_BIAS;
+    g.lin_bias = sp.flags & LIVER_LINEAR_BIAS, g.tied = sp.flags & LIVER_TIED_EMBED;
+
+    // --- views of both worlds (Abstract Resource View) ---------------------------------
+    auto stage_sizes = [&](const liver_layout_t& lay, std::vector<StageSize>& out) {
+        out.resize(lay.pp);
+        const i64 quantum = (i64)lay.dp * lay.pad_multiple;
+        for (int pp = 0; pp < lay.pp; ++pp) {
+            StageSize s;
+            s.n_local = build_column(g, lay.tp, lay.pp, 0, pp).n_local;
+            s.n_pad = (s.n_local + quantum - 1) / quantum * quantum;
+            s.S = s.n_pad / lay.dp;
+            out[pp] = s;
+        }
+    };
+    stage_sizes(S, plan.src_stage);
+    stage_sizes(D, plan.dst_stage);
+
+    const int n_tensors = T_GLOBALS + (int)g.L * T_PER_LAYER;
+    struct SrcRect {
+        Rect r;
+        int tp, pp;
+    };
+    std::vector<std::vector<SrcRect>> by_tensor(n_tensors);  // pruning: only views of the same tensor meet
+    for (int pp = 0; pp < S.pp; ++pp)
+        for (int tp = 0; tp < S.tp; ++tp) {
+            Column c = build_column(g, S.tp, S.pp, tp, pp);
+            for (const Rect& r : c.rects)
+                if (r.canonical) by_tensor[r.tensor].push_back({r, tp, pp});
+        }
+
+    // --- intersect every target view with the source views of its tensor ----------------
+    struct Piece {
+        int slot, s_tp, s_pp;
+        i64 s_off, s_stride, d_off, d_stride, rows, run;
+    };
+    for (int pp = 0; pp < D.pp; ++pp) {
+        if (D.only_pp >= 0 && D.only_pp != pp) continue;
+        for (int tp = 0; tp < D.tp; ++tp) {
+            if (D.only_tp >= 0 && D.only_tp != tp) continue;
+            Column col = build_column(g, D.tp, D.pp, tp, pp);
+            std::vector<Piece> pieces;
+            for (const Rect& d : col.rects) {
+                const i64 dw = d.c1 - d.c0;
+                i64 covered = 0;
+                for (const SrcRect& sr : by_tensor[d.tensor]) {
+                    const Rect& s = sr.r;
+                    const i64 r0 = std::max(d.r0, s.r0), r1 = std::min(d.r1, s.r1);
+                    const i64 c0 = std::max(d.c0, s.c0), c1 = std::min(d.c1, s.c1);
+                    if (r0 >= r1 || c0 >= c1) continue;  // empty intersection: no task
+                    const i64 sw = s.c1 - s.c0;
+                    Piece p{d.slot, sr.tp, sr.pp, s.loff + (r0 - s.r0) * sw + (c0 - s.c0), sw,
+                            d.loff + (r0 - d.r0) * dw + (c0 - d.c0), dw, r1 - r0, c1 - c0};
+                    if (p.rows == 1 || (p.s_stride == p.run && p.d_stride == p.run)) {
+                        p.run *= p.rows;  // dense on both sides: one run
+                        p.rows = 1;
+                        p.s_stride = p.d_stride = p.run;
+                    }
+                    covered += p.rows * p.run;
+                    pieces.push_back(p);
+                }
+                if (covered != (d.r1 - d.r0) * dw) {  // Eq. 1 would be violated
+                    why = "internal: a target view is not tiled by the source views";
+                    return LIVER_E_UNSUPPORTED;
+                }
+            }
+            // merge pieces that continue each other on both sides (same source column)
+            std::sort(pieces.begin(), pieces.end(), [](const Piece& a, const Piece& b) { return a.d_off < b.d_off; });
+            std::vector<Piece> merged;
+            for (const Piece& p : pieces) {
+                if (!merged.empty()) {
+                    Piece& m = merged.back();
+                    const bool same = m.slot == p.slot && m.s_tp == p.s_tp && m.s_pp == p.s_pp;
+                    if (same && m.rows == 1 && p.rows == 1 && p.s_off == m.s_off + m.run && p.d_off == m.d_off + m.run) {
+                        m.run += p.run;
+                        m.s_stride = m.d_stride = m.run;
+                        continue;
+                    }
+                    if (same && m.rows > 1 && p.rows > 1 && m.run == p.run && m.s_stride == p.s_stride &&
+                        m.d_stride == p.d_stride && p.s_off == m.s_off + m.rows * m.s_stride &&
+                        p.d_off == m.d_off + m.rows * m.d_stride) {
+                        m.rows += p.rows;
+                        continue;
+                    }
+                }
+                merged.push_back(p);
+            }
+            for (const Piece& p : merged)
+                expand(p.slot, p.s_tp, p.s_pp, tp, pp, p.s_off, p.s_stride, p.d_off, p.d_stride, p.rows, p.run);
+            zero_padding(col);
+        }
+    }
+    // --- stream order: layer-major, then target rank, kind, target offset ---------------
+    std::stable_sort(entries.begin(), entries.end(), [](const Entry& a, const Entry& b) {
+        const Dst &x = a.dsts[0], &y = b.dsts[0];
+        if (a.slot != b.slot) return a.slot < b.slot;
+        if (x.rank != y.rank) return x.rank < y.rank;
+        if (x.kind != y.kind) return x.kind < y.kind;
+        return x.off < y.off;
+    });
+    emit_lists();
+    int rc = lower(plan.direct, false);
+    if (rc == LIVER_OK) rc = lower(plan.pack, true);
+    if (rc == LIVER_OK) rc = lower(plan.unpack, true);
+    if (rc != LIVER_OK) return rc;
+
+    liver_plan_info_t& info = plan.info;
+    info.n_desc = (i64)plan.direct.pub.size();
+    info.n_desc_pack = (i64)plan.pack.pub.size();
+    info.n_desc_unpack = (i64)plan.unpack.pub.size();
+    info.n_src_ranks = S.tp * S.pp * S.dp;
+    info.n_dst_ranks = D.tp * D.pp * D.dp;
+    plan.used[0].assign((size_t)info.n_src_ranks * 4, 0);
+    plan.used[1].assign((size_t)info.n_dst_ranks * 4, 0);
+    for (const liver_desc_t& d : plan.direct.pub) {
+        const i64 n = d.rows * d.run;
+        if (d.op != LIVER_OP_ZERO) {
+            info.bytes_read += n * elem_bytes(d.src_kind);
+            plan.used[0][(size_t)d.src_rank * 4 + d.src_kind] = 1;
+        } else {
+            info.pad_bytes += n * elem_bytes(d.dst_kind);
+        }
+        info.bytes_written += n * elem_bytes(d.dst_kind);
+        plan.used[1][(size_t)d.dst_rank * 4 + d.dst_kind] = 1;
+    }
+    for (uint8_t u : plan.used[0]) info.n_src_bufs_used += u;
+    for (uint8_t u : plan.used[1]) info.n_dst_bufs_used += u;
+    const uint64_t nd = plan.direct.dev.size(), np = plan.pack.dev.size(), nu = plan.unpack.dev.size();
+    plan.direct.dev_offset = 0;
+    plan.pack.dev_offset = nd * sizeof(DevDesc);
+    plan.unpack.dev_offset = (nd + np) * sizeof(DevDesc);
+    info.table_bytes_device = (i64)((nd + np + nu) * sizeof(DevDesc));
+    return LIVER_OK;
+}
+
+// Direct list: one descriptor per (entry, destination).  Staged lists: walk the
+// entries in stream order, give each its place on the wire, split at chunk ends.
+void Builder::emit_lists() {
+    const i64 B = (i64)plan.chunk_bytes;
+    auto pub = [](const Entry& e, const Dst& d, int chunk) {
+        liver_desc_t o{};
+        o.op = d.op, o.chunk = chunk, o.slot = e.slot;
+        o.src_rank = e.src_rank, o.src_kind = e.src_kind;
+        o.dst_rank = d.rank, o.dst_kind = d.kind;
+        o.src_off = e.src_off, o.src_stride = e.src_stride;
+        o.dst_off = d.off, o.dst_stride = d.stride;
+        o.rows = e.rows, o.run = e.run;
+        return o;
+    };
+    i64 pos = 0;  // byte position on the stream
+    std::vector<Entry> subs;
+    for (const Entry& e : entries) {
+        for (const Dst& d : e.dsts) plan.direct.pub.push_back(pub(e, d, -1));
+        if (e.src_rank < 0) {  // zero fill: no wire bytes; belongs to the chunk the stream is in
+            const i64 chunk = pos == 0 ? 0 : (pos - 1) / B;
+            for (const Dst& d : e.dsts) plan.unpack.pub.push_back(pub(e, d, (int)chunk));
+            continue;
+        }
+        const i64 eb = elem_bytes(e.src_kind), total = e.rows * e.run;
+        i64 p = 0;
+        pos = (pos + 15) / 16 * 16;  // every entry starts 16-byte aligned on the wire
+        while (p < total) {
+            const i64 chunk = pos / B, room = ((chunk + 1) * B - pos) / eb;
+            if (room == 0) {
+                pos = (chunk + 1) * B;
+                continue;
+            }
+            const i64 take = std::min(total - p, room);
+            subs.clear();
+            slice(e, p, p + take, subs);
+            for (const Entry& s : subs) {
+                const i64 wire_elem = (pos - chunk * B) / eb;  // offset inside the chunk, in wire elements
+                liver_desc_t pk{};
+                pk.op = LIVER_OP_COPY, pk.chunk = (int)chunk, pk.slot = s.slot;
+                pk.src_rank = s.src_rank, pk.src_kind = s.src_kind, pk.dst_rank = -1, pk.dst_kind = -1;
+                pk.src_off = s.src_off, pk.src_stride = s.src_stride;
+                pk.dst_off = wire_elem, pk.dst_stride = s.run, pk.rows = s.rows, pk.run = s.run;
+                plan.pack.pub.push_back(pk);
+                for (const Dst& d : s.dsts) {
+                    liver_desc_t un = pub(s, d, (int)chunk);
+                    un.src_rank = -1;  // staging; src_kind keeps the wire element type
+                    un.src_off = wire_elem, un.src_stride = s.run;
+                    plan.unpack.pub.push_back(un);
+                }
+                pos += s.rows * s.run * eb;
+            }
+            p += take;
+        }
+    }
+    plan.info.stream_bytes = pos;
+    plan.info.n_chunks = (pos + B - 1) / B;
+    // chunk order (the unpack list can hold zero fills slightly out of order)
+    auto by_chunk = [](const liver_desc_t& a, const liver_desc_t& b) { return a.chunk < b.chunk; };
+    std::stable_sort(plan.unpack.pub.begin(), plan.unpack.pub.end(), by_chunk);
+}
+
+// Turn public descriptors into device descriptors, grouped into launches.
+int Builder::lower(List& list, bool staged) {
+    const size_t n_chunks = staged ? (size_t)plan.info.n_chunks : 1;
+    list.chunk_pass.assign(n_chunks + 1, 0);
+    int cur_chunk = staged ? -1 : 0;
+    auto new_pass = [&]() {
+        Pass p;
+        p.desc_begin = (uint32_t)list.dev.size();
+        list.passes.push_back(std::move(p));
+    };
+    auto buf_index = [&](Pass& p, BufRef r) -> int {
+        for (size_t i = 0; i < p.bufs.size(); ++i)
+            if (p.bufs[i] == r) return (int)i;
+        return -1;
+    };
+    if (!staged) new_pass();
+    for (const liver_desc_t& d : list.pub) {
+        if (staged && d.chunk != cur_chunk) {
+            for (int c = cur_chunk + 1; c <= d.chunk; ++c) list.chunk_pass[c] = (uint32_t)list.passes.size();
+            cur_chunk = d.chunk;
+            new_pass();
+        }
+        const bool zero = d.op == LIVER_OP_ZERO;
+        BufRef a{int8_t(d.src_rank < 0 ? 2 : 0), int8_t(d.src_rank < 0 ? 0 : d.src_kind), d.src_rank < 0 ? 0 : d.src_rank};
+        BufRef b{int8_t(d.dst_rank < 0 ? 2 : 1), int8_t(d.dst_rank < 0 ? 0 : d.dst_kind), d.dst_rank < 0 ? 0 : d.dst_rank};
+        {
+            Pass& p = list.passes.back();
+            int need = (zero || buf_index(p, a) >= 0 ? 0 : 1) + (buf_index(p, b) >= 0 ? 0 : 1);
+            if ((int)p.bufs.size() + need > MAX_PASS_BUFS) new_pass();
+        }
+        Pass& p = list.passes.back();
+        int ia = 0, ib;
+        if (!zero && (ia = buf_index(p, a)) < 0) {
+            ia = (int)p.bufs.size();
+            p.bufs.push_back(a);
+        }
+        if ((ib = buf_index(p, b)) < 0) {
+            ib = (int)p.bufs.size();
+            p.bufs.push_back(b);
+        }
+        // element sizes on each side
+        const i64 ea = zero ? 0 : elem_bytes(d.src_kind);  // the wire keeps the source type
+        const i64 eb = d.dst_rank < 0 ? ea : elem_bytes(d.dst_kind);
+        DevDesc v{};
+        v.a_off = (uint64_t)(d.src_off * ea);
+        v.b_off = (uint64_t)(d.dst_off * eb);
+        const i64 a_stride = d.src_stride * ea, b_stride = d.dst_stride * eb;
+        const bool rows1 = d.rows == 1;
+        const bool al16 = v.a_off % 16 == 0 && v.b_off % 16 == 0 && (rows1 || (a_stride % 16 == 0 && b_stride % 16 == 0));
+        i64 run_units;
+        if (d.op == LIVER_OP_COPY) {
+            if (ea != eb) {
+                why = "internal: copy between different element sizes";
+                return LIVER_E_UNSUPPORTED;
+            }
+            if (al16 && (d.run * ea) % 16 == 0) v.op = DOP_COPY_V16, run_units = d.run * ea / 16;
+            else v.op = ea == 2 ? DOP_COPY_E2 : DOP_COPY_E4, run_units = d.run;
+        } else if (d.op == LIVER_OP_CAST_BF16) {
+            if (al16 && d.run % 8 == 0) v.op = DOP_CAST_V8, run_units = d.run / 8;
+            else v.op = DOP_CAST_E, run_units = d.run;
+        } else {
+            if (v.b_off % 16 == 0 && (d.run * eb) % 16 == 0) v.op = DOP_ZERO_V16, run_units = d.run * eb / 16;
+            else v.op = eb == 2 ? DOP_ZERO_E2 : DOP_ZERO_E4, run_units = d.run;
+        }
+        const i64 total = d.rows * run_units;
+        if (total <= 0 || total >= (i64(1) << 32) || (!rows1 && (a_stride >= (i64(1) << 32) || b_stride >= (i64(1) << 32)))) {
+            why = "internal: descriptor exceeds 32-bit unit counters";
+            return LIVER_E_UNSUPPORTED;
+        }
+        v.a_stride = rows1 ? 0 : (uint32_t)a_stride;
+        v.b_stride = rows1 ? 0 : (uint32_t)b_stride;
+        v.run = rows1 ? (uint32_t)total : (uint32_t)run_units;
+        v.total = (uint32_t)total;
+        v.a_buf = (uint16_t)ia, v.b_buf = (uint16_t)ib;
+        const uint64_t tiles = ((uint64_t)total + TILE_UNITS - 1) / TILE_UNITS;
+        if ((uint64_t)p.n_tiles + tiles >= (uint64_t(1) << 31)) {
+            why = "internal: more than 2^31 tiles in one launch";
+            return LIVER_E_UNSUPPORTED;
+        }
+        v.tile_begin = p.n_tiles;
+        p.n_tiles += (uint32_t)tiles;
+        p.desc_count += 1;
+        list.dev.push_back(v);
+    }
+    if (staged)
+        for (size_t c = (size_t)cur_chunk + 1; c <= n_chunks; ++c) list.chunk_pass[c] = (uint32_t)list.passes.size();
+    else
+        list.chunk_pass[1] = (uint32_t)list.passes.size();
+    return LIVER_OK;
+}
+
+}  // namespace
+
+int build_plan(liver_plan& plan, std::string& why) {
+    Builder b(plan);
+    int rc = b.run();
+    why = b.why;
+    return rc;
+}
+
+}  // namespace liver

@@ -1,0 +1,219 @@
+"""Host-side checks of the planner through the C ABI (no GPU): its descriptors,
+executed by the NumPy interpreter, must reproduce the oracle bit for bit, write
+every planned target element exactly once, and follow the paper's geometry."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import liver_synth as synth
+import oracle
+import paper_2605_22014_amd as lv
+from interp import lv_objects, descs, run_direct, run_staged, used_dst, DT
+from util import cfg_objects, make_world, tiny_state, corrupt_replicas
+from test_oracle_reshard import ODD, ODD3, ODD6, BRUTE
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "liver.h")).read()
+    names = set(re.findall(r"\b(liver_[a-z_]+)\s*\(", header))
+    assert {"liver_plan_create", "liver_pack", "liver_unpack", "liver_reshard", "liver_plan_destroy"} <= names
+    lib = ctypes.CDLL(lv.library_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def _check(spec, src, dst, world, chunk_bytes, derive=False, **dst_kw):
+    s, a, b = lv_objects(spec, src, dst, derive_bf16=derive, **dst_kw)
+    plan = lv.liver_plan_create(s, a, b, chunk_bytes)
+    info = lv.liver_plan_info(plan)
+    want = oracle.reshard_state(spec, src, dst, world, derive_bf16=derive)
+    for side, lay in ((0, src), (1, dst)):
+        for pp in range(lay.pp):
+            for tp in range(lay.tp):
+                for dp in range(lay.dp):
+                    for k in oracle.KINDS:
+                        n = lv.liver_plan_buffer_bytes(plan, side, lay.rank(tp, pp, dp), k)
+                        assert n == oracle.buffer_elems(spec, lay, tp, pp, k) * np.dtype(DT[k]).itemsize
+    used = used_dst(plan)
+    results = [run_direct(plan, world), run_staged(plan, world),
+               run_staged(plan, world, order=list(range(info.n_chunks))[::-1])]
+    for got, counts in results:
+        for key in got:
+            if key in used:
+                assert (counts[key] == 1).all(), ("not exactly once", key, np.unique(counts[key]))
+                assert np.array_equal(got[key], want[key]), key
+            else:
+                assert not counts[key].any(), ("unplanned buffer written", key)
+    assert info.n_chunks == -(-info.stream_bytes // chunk_bytes)
+    return plan, info, used
+
+
+@pytest.mark.parametrize("derive", [False, True])
+@pytest.mark.parametrize("case", range(len(BRUTE)))
+def test_tiny_odd_models(case, derive):
+    spec, s, d = BRUTE[case]
+    src, dst = oracle.Layout(*s), oracle.Layout(*d)
+    world = make_world(spec, src, tiny_state(spec, seed=case))
+    if case % 2:
+        corrupt_replicas(spec, src, world)
+    _, info, used = _check(spec, src, dst, world, 256 * (1 + case), derive)
+    assert len(used) == dst.n_ranks * 4
+
+
+@pytest.mark.parametrize("chunk_bytes", [4096, 1 << 20, 1 << 30])
+@pytest.mark.parametrize("derive", [False, True])
+def test_tiny_gpt_config(chunk_bytes, derive):
+    cfg, spec, src, dst = cfg_objects("tiny_gpt")
+    state = synth.logical_state(oracle.logical_tensors(spec), synth.SEED_BASE, cfg["dist"])
+    world = make_world(spec, src, state)
+    _, info, _ = _check(spec, src, dst, world, chunk_bytes, derive)
+    if not derive:
+        assert info.stream_bytes == 35_766_272 == info.bytes_read == info.bytes_written
+        assert info.n_chunks == {4096: 8732, 1 << 20: 35, 1 << 30: 1}[chunk_bytes]
+
+
+FILTERS = [dict(only_tp=1), dict(only_pp=0), dict(only_dp=2), dict(only_tp=0, only_pp=1, only_dp=1),
+           dict(kinds=(1, 2, 3)), dict(kinds=(0,)), dict(only_dp=0, kinds=(0, 2))]
+
+
+@pytest.mark.parametrize("derive", [False, True])
+@pytest.mark.parametrize("f", range(len(FILTERS)))
+def test_filtered_plans(f, derive):
+    spec = ODD
+    src, dst = oracle.Layout(1, 2, 2, 4), oracle.Layout(2, 2, 3, 1)
+    world = make_world(spec, src, tiny_state(spec, seed=40 + f))
+    kw = FILTERS[f]
+    _, info, used = _check(spec, src, dst, world, 512, derive, **kw)
+    exp = set()
+    for pp in range(dst.pp):
+        for tp in range(dst.tp):
+            for dp in range(dst.dp):
+                if kw.get("only_tp", tp) == tp and kw.get("only_pp", pp) == pp and kw.get("only_dp", dp) == dp:
+                    exp |= {(dst.rank(tp, pp, dp), k) for k in kw.get("kinds", (0, 1, 2, 3))}
+    assert used == exp
+
+
+def test_gqa_glu_dp_resize_with_padding():
+    """GQA regroup + gated FFN re-block + DP 4 -> 6 cutting through strips, with padding on both sides."""
+    spec = oracle.ModelSpec(n_layers=4, hidden=64, n_q_heads=8, n_kv_heads=4, ffn=96, vocab=128, glu=True)
+    src, dst = oracle.Layout(4, 2, 4, 128), oracle.Layout(2, 4, 6, 128)
+    world = make_world(spec, src, synth.logical_state(oracle.logical_tensors(spec), 3, "normal"))
+    _, info, _ = _check(spec, src, dst, world, 4096)
+    assert info.pad_bytes > 0
+
+
+def test_paper_example_tp4_to_tp8_descriptors():
+    """Section 4.6.1: under TP4 -> TP8 every source rank's column-split shard goes
+    half to target 2s and half to target 2s+1, and nothing moves twice."""
+    from test_oracle_reshard import _golden_tasks
+    spec = oracle.ModelSpec(n_layers=1, hidden=64, n_q_heads=8, n_kv_heads=8, ffn=128, vocab=64)
+    src, dst = oracle.Layout(4, 1, 1, 1), oracle.Layout(8, 1, 1, 1)
+    s, a, b = lv_objects(spec, src, dst, kinds=(1,))
+    plan = lv.liver_plan_create(s, a, b, 1 << 20)
+    sv_s = {tp: {p.name: p for p in oracle.stage_view(spec, src, tp, 0).params} for tp in range(4)}
+    sv_d = {tp: {p.name: p for p in oracle.stage_view(spec, dst, tp, 0).params} for tp in range(8)}
+    tasks = {(t[0], t[1]): t for t in _golden_tasks()}
+    for pname, N in (("L0.o.w", 64), ("L0.fc2.w", 128)):
+        found = {}
+        for d in descs(plan, lv.LIST_DIRECT):
+            ps, pd = sv_s[d.src_rank][pname], sv_d[d.dst_rank][pname]
+            if pd.offset <= d.dst_off < pd.offset + pd.size:
+                assert ps.offset <= d.src_off < ps.offset + ps.size
+                found[(d.src_rank, d.dst_rank)] = d
+                w = N // 8
+                half = tasks[(d.src_rank, d.dst_rank)][4]
+                assert d.rows == 64 and d.run == w and d.src_stride == 2 * w and d.dst_stride == w
+                assert d.src_off - ps.offset == (0 if half == "first" else w) and d.dst_off == pd.offset
+        assert set(found) == set(tasks)          # exactly the paper's 8 tasks
+        assert sum(d.rows * d.run for d in found.values()) == 64 * N      # no redundant movement
+    info = lv.liver_plan_info(plan)
+    assert info.bytes_read == info.bytes_written == sum(
+        oracle.stage_view(spec, dst, tp, 0).n_local for tp in range(8)) * 4
+
+
+def test_pp_only_tasks_are_whole_parameters():
+    """Section 4.6.1 / A.2.3: a PP-only change moves whole shards (full or empty intersection)."""
+    _, spec, _, _ = cfg_objects("tiny_gpt")
+    src, dst = oracle.Layout(2, 1, 1, 128), oracle.Layout(2, 2, 1, 128)
+    s, a, b = lv_objects(spec, src, dst, kinds=(0,))
+    plan = lv.liver_plan_create(s, a, b, 1 << 20)
+    for d in descs(plan, lv.LIST_DIRECT):
+        # dense pieces from the same tp (TP-replicated parameters are read from tp 0)
+        assert d.rows == 1 and d.src_rank % 2 in (d.dst_rank % 2, 0)
+    for tp in range(2):
+        for pp in range(2):
+            sv = oracle.stage_view(spec, dst, tp, pp)
+            pieces = sorted((d.dst_off, d.run) for d in descs(plan, lv.LIST_DIRECT) if d.dst_rank == dst.rank(tp, pp, 0))
+            # pieces tile [0, n_local) and every piece boundary is a parameter boundary
+            bounds = {p.offset for p in sv.params} | {sv.n_local}
+            pos = 0
+            for off, run in pieces:
+                assert off == pos and off in bounds
+                pos += run
+            assert pos == sv.n_local
+
+
+@pytest.mark.parametrize("name", ["gpt2_small", "llama7b", "llama13b_dp", "llama70b_rank"])
+def test_big_config_plan_statistics(name):
+    cfg, spec, src, dst = cfg_objects(name)
+    only = cfg["only"] or {}
+    s, a, b = lv_objects(spec, src, dst, kinds=cfg["kinds"], **{"only_" + k: v for k, v in only.items()})
+    plan = lv.liver_plan_create(s, a, b, cfg["chunk_bytes"])
+    info = lv.liver_plan_info(plan)
+    exp = 0
+    for pp in range(dst.pp):
+        for tp in range(dst.tp):
+            if only.get("tp", tp) != tp or only.get("pp", pp) != pp:
+                continue
+            sv = oracle.stage_view(spec, dst, tp, pp)
+            for dp in range(dst.dp):
+                if only.get("dp", dp) != dp:
+                    continue
+                lo, hi = dp * sv.S, min((dp + 1) * sv.S, sv.n_local)
+                for k in cfg["kinds"]:
+                    exp += sv.n_local * 2 if k == 0 else max(hi - lo, 0) * 4
+    assert info.stream_bytes == info.bytes_read == exp
+    assert info.bytes_written == exp + info.pad_bytes
+    assert info.n_chunks == {"gpt2_small": 31, "llama7b": 352, "llama13b_dp": 25, "llama70b_rank": 16}[name]
+    assert info.table_bytes_device < (2 << 20)           # plan metadata stays around 1 MB (Appendix A.1, Table 3)
+    # every descriptor stays inside its buffers; 16-byte alignment everywhere at real shapes
+    for which in (lv.LIST_DIRECT, lv.LIST_PACK, lv.LIST_UNPACK):
+        for d in descs(plan, which):
+            for side, rank, kind, off, stride in ((0, d.src_rank, d.src_kind, d.src_off, d.src_stride),
+                                                  (1, d.dst_rank, d.dst_kind, d.dst_off, d.dst_stride)):
+                eb = 2 if (kind if rank >= 0 else d.src_kind) == 0 else 4
+                if d.op == lv.OP_ZERO and side == 0:
+                    continue
+                end = (off + (d.rows - 1) * stride + d.run) * eb
+                cap = cfg["chunk_bytes"] if rank < 0 else lv.liver_plan_buffer_bytes(plan, side, rank, kind)
+                assert 0 <= off and end <= cap
+                assert (off * eb) % 16 == 0 and (d.run * eb) % 16 == 0 and (d.rows == 1 or (stride * eb) % 16 == 0)
+
+
+def test_error_codes():
+    _, spec, src, dst = cfg_objects("tiny_gpt")
+    s, a, b = lv_objects(spec, src, dst)
+    for bad_chunk in (0, 100, 4097):
+        with pytest.raises(lv.LiverError) as e:
+            lv.liver_plan_create(s, a, b, bad_chunk)
+        assert e.value.code == -1
+    with pytest.raises(lv.LiverError) as e:
+        lv.liver_plan_create(s, a, lv.Layout(3, 1, 1), 4096)            # 4 heads over TP=3
+    assert e.value.code == -2
+    with pytest.raises(lv.LiverError) as e:
+        lv.liver_plan_create(s, a, lv.Layout(1, 2, 2, only_pp=2), 4096)
+    assert e.value.code == -2
+    with pytest.raises(lv.LiverError) as e:
+        lv.liver_plan_create(s, lv.Layout(2, 1, 2, only_tp=0), b, 4096)
+    assert e.value.code == -2
+    plan = lv.liver_plan_create(s, a, b, 4096)
+    with pytest.raises(lv.LiverError):
+        lv.liver_plan_buffer_bytes(plan, 0, 99, 0)
+    with pytest.raises(lv.LiverError):
+        lv.liver_plan_desc(plan, 0, 10 ** 9)
+    assert "argument" in lv.liver_strerror(-1)
