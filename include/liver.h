@@ -170,10 +170,12 @@ int64_t liver_plan_desc_count(const liver_plan_t* plan, int list);
 int liver_plan_desc(const liver_plan_t* plan, int list, int64_t i, liver_desc_t* out);
 
 /* Launch shape of the copy kernels: grid_blocks workgroups of 256 threads
- * (0 = 8 per compute unit); tile_order 0 = each workgroup walks one contiguous
- * range of tiles, 1 = workgroups interleave tile by tile; cache_hints bit 0 =
- * non-temporal loads, bit 1 = non-temporal stores.  Not thread-safe against
- * concurrent launches of the same plan. */
+ * (0 = default: one per compute unit); tile_order 0 = each workgroup walks one
+ * contiguous range of tiles (default), 1 = workgroups interleave tile by tile;
+ * cache_hints bit 0 = non-temporal loads, bit 1 = non-temporal stores, -1 =
+ * default (direct: both; pack: loads only; unpack: stores only, so that the
+ * staging chunk may stay cache-resident).  Not thread-safe against concurrent
+ * launches of the same plan. */
 int liver_plan_set_launch(liver_plan_t* plan, int grid_blocks, int tile_order, int cache_hints);
 
 /* Algorithm 1, source side: gather chunk `chunk` (0 <= chunk < n_chunks) from the

@@ -393,13 +393,15 @@ def reshard_state(spec: ModelSpec, src: Layout, dst: Layout,
     return out
 
 
-def expected_shards(spec: ModelSpec, lay: Layout, logical: Dict[str, np.ndarray]):
+def expected_shards(spec: ModelSpec, lay: Layout, logical: Dict[str, np.ndarray],
+                    tps: Optional[Iterable[int]] = None, pps: Optional[Iterable[int]] = None):
     """For a subset of logical tensors: yield (tp, pp, stage_view, param, shard)
-    for every physical parameter of world `lay` built only from that subset.
-    Lets a caller verify a few tensors of a very large state one at a time."""
+    for every physical parameter of world `lay` (optionally only rank columns
+    tps x pps) built only from that subset.  Lets a caller verify a few tensors
+    of a very large state one at a time."""
     have = set(logical)
-    for pp in range(lay.pp):
-        for tp in range(lay.tp):
+    for pp in (range(lay.pp) if pps is None else pps):
+        for tp in (range(lay.tp) if tps is None else tps):
             sv = stage_view(spec, lay, tp, pp)
             for prm in sv.params:
                 if all(b.name in have for b in prm.blocks):

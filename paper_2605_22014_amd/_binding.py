@@ -11,6 +11,13 @@ import os
 from dataclasses import dataclass
 from typing import Dict, Optional, Tuple
 
+# torch must be loaded BEFORE libliver.so: the wheel ships its own HIP runtime
+# (libamdhip64.so.7) and the device pointers and streams handed to the library
+# belong to that runtime.  With torch loaded first, the library's dependency on
+# libamdhip64.so.7 resolves to the copy already in the process; the other way
+# round two HIP runtimes would coexist and the library's would see no device.
+import torch  # noqa: F401
+
 PARAM, MASTER, ADAM_M, ADAM_V = 0, 1, 2, 3
 LIST_DIRECT, LIST_PACK, LIST_UNPACK = 0, 1, 2
 OP_COPY, OP_CAST_BF16, OP_ZERO = 0, 1, 2
@@ -190,7 +197,7 @@ def liver_plan_desc(plan: Plan, which: int, i: int) -> Desc:
     return d
 
 
-def liver_plan_set_launch(plan: Plan, grid_blocks: int = 0, tile_order: int = 0, cache_hints: int = 0) -> None:
+def liver_plan_set_launch(plan: Plan, grid_blocks: int = 0, tile_order: int = 0, cache_hints: int = -1) -> None:
     _check(_lib.liver_plan_set_launch(plan.handle, grid_blocks, tile_order, cache_hints))
 
 
@@ -214,7 +221,6 @@ def _table(bufs, n_ranks: int):
 
 def _stream(stream) -> int:
     if stream is None:
-        import torch
         return torch.cuda.current_stream().cuda_stream
     return stream if isinstance(stream, int) else stream.cuda_stream
 

@@ -22,7 +22,7 @@ int n_ranks(const liver_layout_t& l) { return l.tp * l.pp * l.dp; }
 // Resolve the buffers of passes [p0, p1) of `list` and launch them in order.
 // Everything is validated before the first launch, so an error writes nothing.
 int run_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uint32_t p1, const void* const* src_bufs,
-               void* const* dst_bufs, const void* staging, void* hip_stream) {
+               void* const* dst_bufs, const void* staging, void* hip_stream, int default_hints) {
     if (plan->device < 0) return fail(LIVER_E_NO_DEVICE, "plan was created without a HIP device");
     int cur = -1;
     if (hipGetDevice(&cur) != hipSuccess || cur != plan->device)
@@ -35,7 +35,10 @@ int run_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uin
             if (!ptr) return fail(LIVER_E_INVALID_ARG, "a buffer the plan uses is NULL");
             if ((uintptr_t)ptr % 16) return fail(LIVER_E_INVALID_ARG, "buffers must be 16-byte aligned");
         }
-    const uint32_t max_grid = plan->grid_blocks > 0 ? (uint32_t)plan->grid_blocks : (uint32_t)plan->n_cu * 8u;
+    // Default launch shape: one persistent 256-thread workgroup per compute unit.  Measured on MI355X
+    // at the 7B shape, 1-2 workgroups per CU reach the same plateau and more only add DRAM page conflicts.
+    const uint32_t max_grid = plan->grid_blocks > 0 ? (uint32_t)plan->grid_blocks : (uint32_t)plan->n_cu;
+    const int hints = plan->cache_hints >= 0 ? plan->cache_hints : default_hints;
     for (uint32_t p = p0; p < p1; ++p) {
         const liver::Pass& pass = list.passes[p];
         if (pass.n_tiles == 0) continue;
@@ -53,7 +56,7 @@ int run_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uin
         }
         for (; i < (size_t)liver::MAX_PASS_BUFS; ++i) args.bufs[i] = nullptr;
         const uint32_t grid = pass.n_tiles < max_grid ? pass.n_tiles : max_grid;
-        hipError_t e = liver::launch_pass(args, grid, plan->cache_hints, (hipStream_t)hip_stream);
+        hipError_t e = liver::launch_pass(args, grid, hints, (hipStream_t)hip_stream);
         if (e != hipSuccess) return fail(LIVER_E_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
     }
     return LIVER_OK;
@@ -151,7 +154,7 @@ int liver_plan_desc(const liver_plan_t* plan, int list, int64_t i, liver_desc_t*
 }
 
 int liver_plan_set_launch(liver_plan_t* plan, int grid_blocks, int tile_order, int cache_hints) {
-    if (!plan || grid_blocks < 0 || grid_blocks > 65536 || tile_order < 0 || tile_order > 1 || cache_hints < 0 ||
+    if (!plan || grid_blocks < 0 || grid_blocks > 65536 || tile_order < 0 || tile_order > 1 || cache_hints < -1 ||
         cache_hints > 3)
         return fail(LIVER_E_INVALID_ARG, "bad launch shape");
     plan->grid_blocks = grid_blocks, plan->tile_order = tile_order, plan->cache_hints = cache_hints;
@@ -163,7 +166,7 @@ int liver_pack(const liver_plan_t* plan, int chunk, const void* const* src_bufs,
     if (chunk < 0 || chunk >= plan->info.n_chunks) return fail(LIVER_E_INVALID_ARG, "chunk index out of range");
     if ((uintptr_t)staging % 256) return fail(LIVER_E_INVALID_ARG, "staging must be 256-byte aligned");
     return run_passes(plan, plan->pack, plan->pack.chunk_pass[chunk], plan->pack.chunk_pass[chunk + 1], src_bufs, nullptr,
-                      staging, hip_stream);
+                      staging, hip_stream, /*source is streamed once, staging is re-read by unpack*/ 1);
 }
 
 int liver_unpack(const liver_plan_t* plan, int chunk, const void* staging, void* const* dst_bufs, void* hip_stream) {
@@ -171,12 +174,13 @@ int liver_unpack(const liver_plan_t* plan, int chunk, const void* staging, void*
     if (chunk < 0 || chunk >= plan->info.n_chunks) return fail(LIVER_E_INVALID_ARG, "chunk index out of range");
     if ((uintptr_t)staging % 256) return fail(LIVER_E_INVALID_ARG, "staging must be 256-byte aligned");
     return run_passes(plan, plan->unpack, plan->unpack.chunk_pass[chunk], plan->unpack.chunk_pass[chunk + 1], nullptr,
-                      dst_bufs, staging, hip_stream);
+                      dst_bufs, staging, hip_stream, /*staging was just written, targets are streamed*/ 2);
 }
 
 int liver_reshard(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs, void* hip_stream) {
     if (!plan || !src_bufs || !dst_bufs) return fail(LIVER_E_INVALID_ARG, "null argument");
-    return run_passes(plan, plan->direct, 0, (uint32_t)plan->direct.passes.size(), src_bufs, dst_bufs, nullptr, hip_stream);
+    return run_passes(plan, plan->direct, 0, (uint32_t)plan->direct.passes.size(), src_bufs, dst_bufs, nullptr, hip_stream,
+                      /*every byte is touched once*/ 3);
 }
 
 const char* liver_strerror(int code) {

@@ -28,9 +28,16 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int BLOCK = 256;
-constexpr int PER_THREAD = TILE_UNITS / BLOCK;  // 16 units per lane per tile
-constexpr int BATCH = 8;                        // loads in flight per lane
+#ifndef LIVER_BLOCK
+#define LIVER_BLOCK 256
+#endif
+#ifndef LIVER_BATCH
+#define LIVER_BATCH 8
+#endif
+constexpr int BLOCK = LIVER_BLOCK;              // threads per workgroup
+constexpr int PER_THREAD = TILE_UNITS / BLOCK;  // units per lane per tile
+constexpr int BATCH = LIVER_BATCH;              // loads in flight per lane
+static_assert(TILE_UNITS % BLOCK == 0 && PER_THREAD % BATCH == 0, "tile must split evenly into batches");
 
 template <bool NTL, bool NTS>
 struct Mem {

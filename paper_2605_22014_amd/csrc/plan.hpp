@@ -37,7 +37,10 @@ struct DevDesc {
 };
 static_assert(sizeof(DevDesc) == 48, "descriptor layout is shared with the kernels");
 
-constexpr uint32_t TILE_UNITS = 4096;  // units per tile: 64 KiB on the 16-byte paths
+#ifndef LIVER_TILE_UNITS
+#define LIVER_TILE_UNITS 4096
+#endif
+constexpr uint32_t TILE_UNITS = LIVER_TILE_UNITS;  // units per tile: 64 KiB on the 16-byte paths
 constexpr int MAX_PASS_BUFS = 400;     // buffer pointers carried in one launch's arguments
 
 struct BufRef {
@@ -81,7 +84,7 @@ struct liver_plan {
     int device = -1;
     int n_cu = 0;
     // launch shape
-    int grid_blocks = 0, tile_order = 0, cache_hints = 0;
+    int grid_blocks = 0, tile_order = 0, cache_hints = -1;  // 0 / -1 = library defaults
 };
 
 namespace liver {

@@ -1,0 +1,154 @@
+"""Parity at the full sizes of the large configurations, in the launch shape the
+benchmark times (library defaults): the state is generated in HBM, resharded by
+the HIP path (direct, then staged), and a sample of logical tensors -- first,
+middle and last layers, embeddings, head -- is gathered and re-split by the CPU
+oracle and compared bit for bit; plus size-independent properties (zero padding,
+untouched source)."""
+import numpy as np
+import pytest
+import torch
+
+import liver_synth as synth
+import oracle
+import paper_2605_22014_amd as lv
+from util import cfg_objects
+
+pytestmark = pytest.mark.gpu
+NP = {0: np.uint16, 1: np.uint32, 2: np.uint32, 3: np.uint32}
+
+
+def _setup(name):
+    cfg, ospec, osrc, odst = cfg_objects(name)
+    only = cfg["only"] or {}
+    spec = lv.ModelSpec(**cfg["spec"])
+    src = lv.Layout(pad_multiple=cfg["pad_multiple"], **cfg["src"])
+    dst = lv.Layout(pad_multiple=cfg["pad_multiple"], kinds=tuple(cfg["kinds"]),
+                    **{"only_" + k: v for k, v in only.items()}, **cfg["dst"])
+    plan = lv.liver_plan_create(spec, src, dst, cfg["chunk_bytes"])
+    sizes = {}
+    for pp in range(src.pp):
+        for tp in range(src.tp):
+            if any(lv.liver_plan_buffer_used(plan, 0, src.rank(tp, pp, d), k) for d in range(src.dp) for k in range(4)):
+                for d in range(src.dp):
+                    n = lv.liver_plan_buffer_bytes(plan, 0, src.rank(tp, pp, d), lv.MASTER) // 4
+                    assert n == oracle.buffer_elems(ospec, osrc, tp, pp, oracle.MASTER)
+                    sizes[((tp, pp), d)] = n
+    gen = synth.fill_device_world(sizes, src.dp, synth.SEED_BASE)
+    src_bufs = {}
+    for (col, d) in sizes:
+        r = src.rank(col[0], col[1], d)
+        for k in (1, 2, 3):
+            src_bufs[(r, k)] = gen[(col, d, k)]
+        src_bufs[(r, 0)] = gen[(col, "param")]
+    return cfg, only, ospec, osrc, odst, plan, src, dst, src_bufs
+
+
+def _fresh_dst(plan, dst):
+    out = {}
+    for r in range(dst.n_ranks):
+        for k in range(4):
+            if lv.liver_plan_buffer_used(plan, 1, r, k):
+                n = lv.liver_plan_buffer_bytes(plan, 1, r, k) // (2 if k == 0 else 4)
+                out[(r, k)] = torch.full((n,), -23131 if k == 0 else -1515870811,
+                                         dtype=torch.int16 if k == 0 else torch.int32, device="cuda")
+    return out
+
+
+def _expected(cfg, only, ospec, osrc, odst, src_bufs, names):
+    """[(kind, tp, pp, stage_view, param, shard)] for the sampled tensors, from the oracle."""
+    def read(rank, kind, lo, hi):
+        if (rank, kind) not in src_bufs:                 # a source rank this filtered plan never reads
+            return np.zeros(hi - lo, NP[kind])
+        return src_bufs[(rank, kind)][lo:hi].view(torch.int16 if kind == 0 else torch.int32).cpu().numpy().view(NP[kind])
+    tps = [only["tp"]] if "tp" in only else None
+    pps = [only["pp"]] if "pp" in only else None
+    out = []
+    for k in cfg["kinds"]:
+        logical = oracle.gather_logical(ospec, osrc, k, read, names=names)
+        out += [(k,) + t for t in oracle.expected_shards(ospec, odst, logical, tps, pps)]
+        print(f"  oracle: kind {k} gathered and split", flush=True)
+    return out
+
+
+def _compare(expected, only, odst, dst_bufs, what):
+    n_checked = 0
+    for k, tp, pp, sv, prm, shard in expected:
+        flat = shard.ravel()
+        for d in range(odst.dp):
+            if only.get("dp", d) != d:
+                continue
+            r = odst.rank(tp, pp, d)
+            if k == 0:
+                a, b, part = prm.offset, prm.offset + prm.size, flat
+            else:
+                lo, hi = max(prm.offset, d * sv.S), min(prm.offset + prm.size, (d + 1) * sv.S)
+                if lo >= hi:
+                    continue
+                part, a, b = flat[lo - prm.offset:hi - prm.offset], lo - d * sv.S, hi - d * sv.S
+            got = dst_bufs[(r, k)][a:b].cpu().numpy().view(NP[k])
+            assert np.array_equal(got, part), (what, prm.name, "rank", r, "kind", k)
+            n_checked += part.size
+    assert n_checked > 0
+    return n_checked
+
+
+def _pads_zero(only, ospec, odst, dst_bufs):
+    for (r, k), t in dst_bufs.items():
+        pp = r // (odst.tp * odst.dp)
+        d = (r // odst.tp) % odst.dp
+        sv = oracle.stage_view(ospec, odst, r % odst.tp, pp)
+        lo = sv.n_local if k == 0 else max(sv.n_local - d * sv.S, 0)
+        if lo < t.numel():
+            assert not t[lo:].any().item(), ("padding not zero", r, k)
+
+
+def _run(name, names):
+    print(f"{name}: generating state in HBM", flush=True)
+    cfg, only, ospec, osrc, odst, plan, src, dst, src_bufs = _setup(name)
+    sums = {key: int(t.view(torch.int16 if key[1] == 0 else torch.int32).sum(dtype=torch.int64)) for key, t in src_bufs.items()}
+    info = lv.liver_plan_info(plan)
+    print(f"{name}: direct reshard, {info.n_desc} descriptors, {(info.bytes_read + info.bytes_written) / 1e9:.2f} GB", flush=True)
+    dst_bufs = _fresh_dst(plan, dst)
+    lv.liver_reshard(plan, src_bufs, dst_bufs)
+    torch.cuda.synchronize()
+    print(f"{name}: oracle on {len(names)} tensors", flush=True)
+    expected = _expected(cfg, only, ospec, osrc, odst, src_bufs, names)
+    n = _compare(expected, only, odst, dst_bufs, "direct")
+    _pads_zero(only, ospec, odst, dst_bufs)
+    print(f"{name}: direct ok on {n} sampled elements; staged path, {info.n_chunks} chunks", flush=True)
+    del dst_bufs
+    dst_bufs = _fresh_dst(plan, dst)
+    staging = torch.empty(cfg["chunk_bytes"], dtype=torch.uint8, device="cuda")
+    for c in range(info.n_chunks):
+        lv.liver_pack(plan, c, src_bufs, staging)
+        lv.liver_unpack(plan, c, staging, dst_bufs)
+    torch.cuda.synchronize()
+    _compare(expected, only, odst, dst_bufs, "staged")
+    _pads_zero(only, ospec, odst, dst_bufs)
+    for key, t in src_bufs.items():          # source world untouched
+        assert int(t.view(torch.int16 if key[1] == 0 else torch.int32).sum(dtype=torch.int64)) == sums[key], key
+    print(f"{name}: staged ok", flush=True)
+
+
+def _layer(ospec, l, leaves=None):
+    return [n for n in oracle.logical_tensors(ospec) if n.startswith(f"L{l}.") and (leaves is None or n.split(".", 1)[1] in leaves)]
+
+
+def test_llama7b_tp8_to_tp4pp2():
+    _, ospec, _, _ = cfg_objects("llama7b")
+    names = ["embed.word", "final_norm.w", "lm_head.w"] + _layer(ospec, 0) + _layer(ospec, 15, ("ln1.w", "q.w", "o.w", "down.w")) \
+        + _layer(ospec, 16, ("k.w", "v.w", "gate.w", "ln2.w")) + _layer(ospec, 31, ("o.w", "up.w", "down.w"))
+    _run("llama7b", names)
+
+
+def test_llama13b_dp8_to_dp6():
+    _, ospec, _, _ = cfg_objects("llama13b_dp")
+    # target rank (tp 0, pp 1, dp 2) owns flat elements of layers 26..30 of its stage
+    names = _layer(ospec, 26, ("o.w", "gate.w", "up.w", "down.w")) + _layer(ospec, 28) + _layer(ospec, 30, ("ln1.w", "q.w", "k.w", "v.w", "o.w"))
+    _run("llama13b_dp", names)
+
+
+def test_llama70b_one_target_rank():
+    _, ospec, _, _ = cfg_objects("llama70b_rank")
+    names = _layer(ospec, 30) + _layer(ospec, 39, ("q.w", "k.w", "v.w", "o.w", "ln2.w"))
+    _run("llama70b_rank", names)
