@@ -23,9 +23,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM traffic per direct-reshard launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
-# what the same counters read for a plain copy of known size; see profiles/.  None until measured.
-MEASURED_TRAFFIC_GB = {}
+# HBM traffic (GB) per direct-reshard launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled
+# by what the same counters read for a plain 1 GiB copy (FETCH x1.99991, WRITE x1.0).
+MEASURED_TRAFFIC_GB = {"llama7b": 188.73}   # profiles/liver_copy_kernel_llama7b_direct.md
 
 
 def main():
@@ -190,11 +190,12 @@ def main():
     print(json.dumps(out))
 
 
-def cpu_baseline(cfg, src_bufs, dst_bufs, src, dst):
+def cpu_baseline(cfg, src_bufs, dst_bufs, src, dst, n_layers_sampled=8):
     """The CPU oracle (gather to full logical tensors, re-split) timed on a bounded
-    sample of the same workload: the tensors of one transformer layer (layer 0),
-    all buffer kinds, inputs already in host memory.  Its output also checks the
-    GPU result for that layer."""
+    sample of the same workload: all tensors of a few transformer layers spread
+    over the model (of the planned target stage for a filtered plan), all buffer
+    kinds, inputs already in host memory, one layer at a time.  Its output also
+    checks the GPU result for those layers."""
     import numpy as np
     import torch
     import oracle
@@ -202,64 +203,66 @@ def cpu_baseline(cfg, src_bufs, dst_bufs, src, dst):
     osrc = oracle.Layout(pad_multiple=cfg["pad_multiple"], **cfg["src"])
     odst = oracle.Layout(pad_multiple=cfg["pad_multiple"], **cfg["dst"])
     only = cfg["only"] or {}
-    pp_dst = only.get("pp", 0)
-    layer = pp_dst * (ospec.n_layers // odst.pp)
-    names = [n for n in oracle.logical_tensors(ospec) if n.startswith(f"L{layer}.")]
-    pp_src = layer // (ospec.n_layers // osrc.pp)
+    per_dst = ospec.n_layers // odst.pp
+    first, count = (only["pp"] * per_dst, per_dst) if "pp" in only else (0, ospec.n_layers)
+    n = min(n_layers_sampled, count)
+    layers = sorted({first + (i * count) // n for i in range(n)})
+    tps = [only["tp"]] if "tp" in only else None
+    pps = [only["pp"]] if "pp" in only else None
     NP = {0: np.uint16, 1: np.uint32, 2: np.uint32, 3: np.uint32}
-    # host copies of the source ranges that hold this layer
-    host = {}
-    for tp in range(osrc.tp):
-        sv = oracle.stage_view(ospec, osrc, tp, pp_src)
-        ps = [p for p in sv.params if p.name.startswith(f"L{layer}.")]
-        lo, hi = min(p.offset for p in ps), max(p.offset + p.size for p in ps)
-        for d in range(osrc.dp):
-            r = osrc.rank(tp, pp_src, d)
-            for k in cfg["kinds"]:
-                if (r, k) not in src_bufs:
-                    continue
-                a, b = (lo, hi) if k == 0 else (max(lo - d * sv.S, 0), min(hi - d * sv.S, sv.S))
-                if a < b:
-                    host[(r, k)] = (a, src_bufs[(r, k)][a:b].view(torch.int16 if k == 0 else torch.int32).cpu().numpy().view(NP[k]))
+    secs, nbytes = 0.0, 0
+    for layer in layers:
+        names = [t for t in oracle.logical_tensors(ospec) if t.startswith(f"L{layer}.")]
+        pp_src = layer // (ospec.n_layers // osrc.pp)
+        host = {}                       # host copies of the source ranges that hold this layer
+        for tp in range(osrc.tp):
+            sv = oracle.stage_view(ospec, osrc, tp, pp_src)
+            ps = [p for p in sv.params if p.name.startswith(f"L{layer}.")]
+            lo, hi = min(p.offset for p in ps), max(p.offset + p.size for p in ps)
+            for d in range(osrc.dp):
+                r = osrc.rank(tp, pp_src, d)
+                for k in cfg["kinds"]:
+                    a, b = (lo, hi) if k == 0 else (max(lo - d * sv.S, 0), min(hi - d * sv.S, sv.S))
+                    if a >= b:
+                        continue
+                    if (r, k) in src_bufs:
+                        t = src_bufs[(r, k)][a:b].view(torch.int16 if k == 0 else torch.int32)
+                        host[(r, k)] = (a, t.cpu().numpy().view(NP[k]))
+                    else:               # a source rank this filtered plan never reads
+                        host[(r, k)] = (a, np.zeros(b - a, NP[k]))
 
-    def read(rank, kind, lo, hi):
-        base, arr = host[(rank, kind)]
-        assert base <= lo and hi - base <= arr.size
-        return arr[lo - base:hi - base]
+        def read(rank, kind, lo, hi):
+            base, arr = host[(rank, kind)]
+            assert base <= lo and hi - base <= arr.size
+            return arr[lo - base:hi - base]
 
-    t = time.perf_counter()
-    expected, nbytes = [], 0
-    for k in cfg["kinds"]:
-        logical = oracle.gather_logical(ospec, osrc, k, read, names=names)
-        for tp, pp, sv, prm, shard in oracle.expected_shards(ospec, odst, logical):
-            if only.get("tp", tp) != tp or only.get("pp", pp) != pp:
-                continue
-            expected.append((k, tp, pp, sv, prm, shard))
-            nbytes += shard.nbytes
-    secs = time.perf_counter() - t
-    # parity of the GPU result on the same sample
-    ok = True
-    for k, tp, pp, sv, prm, shard in expected:
-        flat = shard.ravel()
-        for d in range(odst.dp):
-            if only.get("dp", d) != d:
-                continue
-            r = odst.rank(tp, pp, d)
-            if k == 0:
-                a, b, part = prm.offset, prm.offset + prm.size, flat
-            else:
-                a, b = max(prm.offset, d * sv.S), min(prm.offset + prm.size, (d + 1) * sv.S)
-                if a >= b:
+        t0 = time.perf_counter()
+        expected = []
+        for k in cfg["kinds"]:
+            logical = oracle.gather_logical(ospec, osrc, k, read, names=names)
+            expected += [(k,) + e for e in oracle.expected_shards(ospec, odst, logical, tps, pps)]
+        secs += time.perf_counter() - t0
+        for k, tp, pp, sv, prm, shard in expected:      # parity of the GPU result on the same sample
+            flat = shard.ravel()
+            for d in range(odst.dp):
+                if only.get("dp", d) != d:
                     continue
-                part = flat[a - prm.offset:b - prm.offset]
-                a, b = a - d * sv.S, b - d * sv.S
-            eb = 2 if k == 0 else 4
-            got = dst_bufs[(r, k)][a * eb:b * eb].cpu().numpy().view(NP[k])
-            ok = ok and np.array_equal(got, part)
-    assert ok, "GPU result differs from the oracle on the sampled layer"
+                r = odst.rank(tp, pp, d)
+                if k == 0:
+                    a, b, part = prm.offset, prm.offset + prm.size, flat
+                else:
+                    a, b = max(prm.offset, d * sv.S), min(prm.offset + prm.size, (d + 1) * sv.S)
+                    if a >= b:
+                        continue
+                    part = flat[a - prm.offset:b - prm.offset]
+                    a, b = a - d * sv.S, b - d * sv.S
+                eb = 2 if k == 0 else 4
+                got = dst_bufs[(r, k)][a * eb:b * eb].cpu().numpy().view(NP[k])
+                assert np.array_equal(got, part), f"GPU result differs from the oracle: layer {layer} {prm.name} kind {k}"
+                nbytes += part.nbytes
     return {"value": round(2 * nbytes / secs / 1e9, 3), "unit": "GB/s", "cores": _threads_used(), "kind": "oracle",
-            "sample": f"all tensors of layer {layer}, kinds {list(cfg['kinds'])}: {nbytes / 1e9:.2f} GB of target "
-                      f"state gathered and re-split in {secs:.2f} s; GPU result equal on this sample",
+            "sample": f"all tensors of layers {layers}, kinds {list(cfg['kinds'])}: {nbytes / 1e9:.2f} GB of target "
+                      f"state gathered and re-split in {secs:.2f} s of CPU time; GPU result equal on this sample",
             "host_cores_available": len(os.sched_getaffinity(0))}
 
 

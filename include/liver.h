@@ -199,6 +199,15 @@ int liver_reshard(const liver_plan_t* plan, const void* const* src_bufs, void* c
 
 const char* liver_strerror(int code);
 
+/* Debugging aid, never called by the entry points above (there is no CPU
+ * fallback): executes the plan's LOWERED descriptor tables -- what the kernels
+ * would run for list `list` (LIVER_LIST_*; `chunk` is ignored for the direct
+ * list) -- on HOST memory, unit by unit, and returns LIVER_E_HIP instead of
+ * performing any access that is out of bounds or misaligned.  Buffers are host
+ * arrays with the sizes liver_plan_buffer_bytes reports; staging has chunk_bytes. */
+int liver_debug_emulate_host(const liver_plan_t* plan, int list, int chunk, const void* const* src_bufs,
+                             void* const* dst_bufs, void* staging);
+
 #ifdef __cplusplus
 }
 #endif

@@ -125,6 +125,7 @@ def _load() -> C.CDLL:
     lib.liver_pack.argtypes = [P, C.c_int, C.POINTER(P), P, P]
     lib.liver_unpack.argtypes = [P, C.c_int, P, C.POINTER(P), P]
     lib.liver_reshard.argtypes = [P, C.POINTER(P), C.POINTER(P), P]
+    lib.liver_debug_emulate_host.argtypes = [P, C.c_int, C.c_int, C.POINTER(P), C.POINTER(P), P]
     lib.liver_strerror.argtypes = [C.c_int]
     lib.liver_strerror.restype = C.c_char_p
     return lib
@@ -236,6 +237,18 @@ def liver_unpack(plan: Plan, chunk: int, staging, dst_bufs, stream=None) -> None
 def liver_reshard(plan: Plan, src_bufs, dst_bufs, stream=None) -> None:
     _check(_lib.liver_reshard(plan.handle, _table(src_bufs, plan.src.n_ranks), _table(dst_bufs, plan.dst.n_ranks),
                               _stream(stream)))
+
+
+def liver_debug_emulate_host(plan: Plan, which: int, chunk: int, src_bufs, dst_bufs, staging) -> None:
+    """Run the lowered descriptors on HOST arrays ({(rank, kind): numpy array}); test aid."""
+    def table(bufs, n):
+        arr = (C.c_void_p * (n * 4))()
+        for (rank, kind), a in (bufs or {}).items():
+            arr[rank * 4 + kind] = a.ctypes.data
+        return arr
+    _check(_lib.liver_debug_emulate_host(plan.handle, which, chunk, table(src_bufs, plan.src.n_ranks),
+                                         table(dst_bufs, plan.dst.n_ranks),
+                                         staging.ctypes.data if staging is not None else None))
 
 
 def make_table(bufs: Dict[Tuple[int, int], object], n_ranks: int):

@@ -12,7 +12,8 @@
 //     sequential), all descriptor reads are wave-uniform;
 //   * every lane moves 16 bytes per access (global_load/store_dwordx4), 64 lanes
 //     cover 1 KiB contiguous, 8 independent loads are in flight per lane before
-//     the first store;
+//     the first store; the fused cast reads 16 B of fp32 once and writes the
+//     fp32 copy (16 B) and the bf16 weights (8 B) from the same registers;
 //   * runs (row-parallel strips, per-head QKV groups) are multiples of 16 bytes
 //     in every real configuration, so strided pieces are linearised over
 //     (row, column) and stay fully coalesced on both sides without staging in
@@ -61,94 +62,79 @@ __device__ __forceinline__ uint32_t bf16_rne(uint32_t u) {
     return r & 0xFFFFu;
 }
 
-// Unit `u` of a piece: row r = u / run, column c = u % run.
+// Unit `u` of a piece sits at row r = u / run, column c = u % run; a dense piece
+// (one run) is row 0.  Byte offset in a buffer = r * stride + c * unit_bytes.
 struct Geom {
-    uint32_t run, a_stride, b_stride;
+    uint32_t run;
     bool dense;
-    __device__ __forceinline__ void locate(uint32_t u, uint64_t a_unit, uint64_t b_unit, uint64_t& ao,
-                                           uint64_t& bo) const {
+    __device__ __forceinline__ void locate(uint32_t u, uint32_t& r, uint32_t& c) const {
         if (dense) {
-            ao = (uint64_t)u * a_unit;
-            bo = (uint64_t)u * b_unit;
+            r = 0;
+            c = u;
         } else {
-            const uint32_t r = u / run, c = u - r * run;
-            ao = (uint64_t)r * a_stride + (uint64_t)c * a_unit;
-            bo = (uint64_t)r * b_stride + (uint64_t)c * b_unit;
+            r = u / run;
+            c = u - r * run;
         }
     }
 };
+__device__ __forceinline__ uint64_t at(uint32_t r, uint32_t c, uint32_t stride, uint32_t unit) {
+    return (uint64_t)r * stride + (uint64_t)c * unit;
+}
 
-template <class M>
-__device__ __forceinline__ void tile_copy_v16(const Geom& g, uint32_t u0, uint32_t n, const char* a, char* b) {
+__device__ __forceinline__ u32x2 pack_bf16x4(u32x4 v) {
+    u32x2 o;
+    o.x = bf16_rne(v.x) | (bf16_rne(v.y) << 16);
+    o.y = bf16_rne(v.z) | (bf16_rne(v.w) << 16);
+    return o;
+}
+
+// FUSE 0: B <- A (16 B units).  FUSE 1: C <- bf16(A).  FUSE 2: B <- A and C <- bf16(A).
+template <class M, int FUSE>
+__device__ __forceinline__ void tile_v16(const Geom& g, const DevDesc& D, uint32_t u0, uint32_t n, const char* a,
+                                         char* b, char* c) {
     const uint32_t tid = threadIdx.x;
+    auto out = [&](uint32_t r, uint32_t col, u32x4 v) {
+        if (FUSE != 1) M::st((u32x4*)(b + at(r, col, D.b_stride, 16)), v);
+        if (FUSE != 0) M::st((u32x2*)(c + at(r, col, D.c_stride, 8)), pack_bf16x4(v));
+    };
     if (n == TILE_UNITS) {
 #pragma unroll
         for (int k = 0; k < PER_THREAD; k += BATCH) {
             u32x4 v[BATCH];
-            uint64_t bo[BATCH];
+            uint32_t r[BATCH], col[BATCH];
 #pragma unroll
             for (int j = 0; j < BATCH; ++j) {
-                uint64_t ao;
-                g.locate(u0 + tid + (k + j) * BLOCK, 16, 16, ao, bo[j]);
-                v[j] = M::ld((const u32x4*)(a + ao));
+                g.locate(u0 + tid + (k + j) * BLOCK, r[j], col[j]);
+                v[j] = M::ld((const u32x4*)(a + at(r[j], col[j], D.a_stride, 16)));
             }
 #pragma unroll
-            for (int j = 0; j < BATCH; ++j) M::st((u32x4*)(b + bo[j]), v[j]);
+            for (int j = 0; j < BATCH; ++j) out(r[j], col[j], v[j]);
         }
     } else {
         for (uint32_t i = tid; i < n; i += BLOCK) {
-            uint64_t ao, bo;
-            g.locate(u0 + i, 16, 16, ao, bo);
-            M::st((u32x4*)(b + bo), M::ld((const u32x4*)(a + ao)));
-        }
-    }
-}
-
-template <class M>
-__device__ __forceinline__ void tile_cast_v8(const Geom& g, uint32_t u0, uint32_t n, const char* a, char* b) {
-    constexpr int CB = 4;
-    for (uint32_t i0 = threadIdx.x; i0 < n; i0 += BLOCK * CB) {
-        u32x4 lo[CB], hi[CB];
-        uint64_t bo[CB];
-#pragma unroll
-        for (int j = 0; j < CB; ++j) {
-            const uint32_t i = i0 + j * BLOCK;
-            if (i < n) {
-                uint64_t ao;
-                g.locate(u0 + i, 32, 16, ao, bo[j]);
-                lo[j] = M::ld((const u32x4*)(a + ao));
-                hi[j] = M::ld((const u32x4*)(a + ao + 16));
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < CB; ++j) {
-            const uint32_t i = i0 + j * BLOCK;
-            if (i < n) {
-                u32x4 o;
-                o.x = bf16_rne(lo[j].x) | (bf16_rne(lo[j].y) << 16);
-                o.y = bf16_rne(lo[j].z) | (bf16_rne(lo[j].w) << 16);
-                o.z = bf16_rne(hi[j].x) | (bf16_rne(hi[j].y) << 16);
-                o.w = bf16_rne(hi[j].z) | (bf16_rne(hi[j].w) << 16);
-                M::st((u32x4*)(b + bo[j]), o);
-            }
+            uint32_t r, col;
+            g.locate(u0 + i, r, col);
+            out(r, col, M::ld((const u32x4*)(a + at(r, col, D.a_stride, 16))));
         }
     }
 }
 
 template <class T>
-__device__ __forceinline__ void tile_copy_elem(const Geom& g, uint32_t u0, uint32_t n, const char* a, char* b) {
+__device__ __forceinline__ void tile_copy_elem(const Geom& g, const DevDesc& D, uint32_t u0, uint32_t n, const char* a,
+                                               char* b) {
     for (uint32_t i = threadIdx.x; i < n; i += BLOCK) {
-        uint64_t ao, bo;
-        g.locate(u0 + i, sizeof(T), sizeof(T), ao, bo);
-        *(T*)(b + bo) = *(const T*)(a + ao);
+        uint32_t r, c;
+        g.locate(u0 + i, r, c);
+        *(T*)(b + at(r, c, D.b_stride, sizeof(T))) = *(const T*)(a + at(r, c, D.a_stride, sizeof(T)));
     }
 }
 
-__device__ __forceinline__ void tile_cast_elem(const Geom& g, uint32_t u0, uint32_t n, const char* a, char* b) {
+__device__ __forceinline__ void tile_cast_elem(const Geom& g, const DevDesc& D, uint32_t u0, uint32_t n, const char* a,
+                                               char* b) {
     for (uint32_t i = threadIdx.x; i < n; i += BLOCK) {
-        uint64_t ao, bo;
-        g.locate(u0 + i, 4, 2, ao, bo);
-        *(uint16_t*)(b + bo) = (uint16_t)bf16_rne(*(const uint32_t*)(a + ao));
+        uint32_t r, c;
+        g.locate(u0 + i, r, c);
+        *(uint16_t*)(b + at(r, c, D.b_stride, 2)) = (uint16_t)bf16_rne(*(const uint32_t*)(a + at(r, c, D.a_stride, 4)));
     }
 }
 
@@ -194,15 +180,16 @@ __global__ __launch_bounds__(BLOCK) void liver_copy_kernel(const PassArgs args) 
         const uint32_t u0 = (t - D.tile_begin) * TILE_UNITS;
         const uint32_t left = D.total - u0;
         const uint32_t n = left < TILE_UNITS ? left : TILE_UNITS;
-        Geom g{D.run, D.a_stride, D.b_stride, D.run == D.total};
+        const Geom g{D.run, D.run == D.total};
         const char* a = args.bufs[D.a_buf] + D.a_off;
         char* b = args.bufs[D.b_buf] + D.b_off;
         switch (D.op) {
-            case DOP_COPY_V16: tile_copy_v16<M>(g, u0, n, a, b); break;
-            case DOP_CAST_V8: tile_cast_v8<M>(g, u0, n, a, b); break;
-            case DOP_COPY_E2: tile_copy_elem<uint16_t>(g, u0, n, a, b); break;
-            case DOP_COPY_E4: tile_copy_elem<uint32_t>(g, u0, n, a, b); break;
-            case DOP_CAST_E: tile_cast_elem(g, u0, n, a, b); break;
+            case DOP_COPY_V16: tile_v16<M, 0>(g, D, u0, n, a, b, nullptr); break;
+            case DOP_CAST_V4: tile_v16<M, 1>(g, D, u0, n, a, nullptr, args.bufs[D.c_buf] + D.c_off); break;
+            case DOP_COPYCAST_V4: tile_v16<M, 2>(g, D, u0, n, a, b, args.bufs[D.c_buf] + D.c_off); break;
+            case DOP_COPY_E2: tile_copy_elem<uint16_t>(g, D, u0, n, a, b); break;
+            case DOP_COPY_E4: tile_copy_elem<uint32_t>(g, D, u0, n, a, b); break;
+            case DOP_CAST_E: tile_cast_elem(g, D, u0, n, a, b); break;
             case DOP_ZERO_V16: tile_zero<u32x4>(u0, n, b); break;
             case DOP_ZERO_E2: tile_zero<uint16_t>(u0, n, b); break;
             case DOP_ZERO_E4: tile_zero<uint32_t>(u0, n, b); break;

@@ -12,30 +12,34 @@ namespace liver {
 // One strided 2-D copy in "units".  A unit is 16 bytes on the vector paths and
 // one element on the element paths (unaligned pieces of odd-sized models).
 enum DevOp : uint32_t {
-    DOP_COPY_V16 = 0,  // 16 B in, 16 B out
-    DOP_COPY_E2 = 1,   // one 2-byte element
-    DOP_COPY_E4 = 2,   // one 4-byte element
-    DOP_CAST_V8 = 3,   // 8 fp32 (32 B) in, 8 bf16 (16 B) out
-    DOP_CAST_E = 4,    // one fp32 in, one bf16 out
-    DOP_ZERO_V16 = 5,  // 16 B of zeros out
+    DOP_COPY_V16 = 0,     // 16 B in, 16 B out
+    DOP_COPY_E2 = 1,      // one 2-byte element
+    DOP_COPY_E4 = 2,      // one 4-byte element
+    DOP_CAST_V4 = 3,      // 4 fp32 (16 B) in, 4 bf16 (8 B) out
+    DOP_CAST_E = 4,       // one fp32 in, one bf16 out
+    DOP_ZERO_V16 = 5,     // 16 B of zeros out
     DOP_ZERO_E2 = 6,
     DOP_ZERO_E4 = 7,
+    DOP_COPYCAST_V4 = 8,  // 4 fp32 in; 4 fp32 out to B and 4 bf16 out to C (source read once)
 };
 
 struct DevDesc {
     uint64_t a_off;       // byte offset of the piece in its source buffer
     uint64_t b_off;       // byte offset of the piece in its target buffer
+    uint64_t c_off;       // second target (COPYCAST only)
     uint32_t a_stride;    // bytes between rows (unused when run == total)
     uint32_t b_stride;
+    uint32_t c_stride;
     uint32_t run;         // units per row
     uint32_t total;       // rows * run
     uint32_t tile_begin;  // first tile of this descriptor inside its pass
     uint16_t a_buf;       // index into the pass's buffer table (unused for ZERO)
     uint16_t b_buf;
-    uint32_t op;          // DevOp
-    uint32_t reserved;
+    uint16_t c_buf;
+    uint16_t op;          // DevOp
+    uint64_t reserved;
 };
-static_assert(sizeof(DevDesc) == 48, "descriptor layout is shared with the kernels");
+static_assert(sizeof(DevDesc) == 64, "descriptor layout is shared with the kernels");
 
 #ifndef LIVER_TILE_UNITS
 #define LIVER_TILE_UNITS 4096
@@ -63,6 +67,7 @@ struct List {
     std::vector<Pass> passes;
     std::vector<uint32_t> chunk_pass;   // staged lists: passes of chunk k are [chunk_pass[k], chunk_pass[k+1])
     uint64_t dev_offset = 0;            // byte offset of dev[] inside the plan's device table
+    int64_t hbm_read = 0, hbm_written = 0;  // bytes the lowered descriptors read / write
 };
 
 struct StageSize {

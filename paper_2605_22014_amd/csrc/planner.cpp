@@ -443,16 +443,12 @@ int Builder::run() {
     plan.used[0].assign((size_t)info.n_src_ranks * 4, 0);
     plan.used[1].assign((size_t)info.n_dst_ranks * 4, 0);
     for (const liver_desc_t& d : plan.direct.pub) {
-        const i64 n = d.rows * d.run;
-        if (d.op != LIVER_OP_ZERO) {
-            info.bytes_read += n * elem_bytes(d.src_kind);
-            plan.used[0][(size_t)d.src_rank * 4 + d.src_kind] = 1;
-        } else {
-            info.pad_bytes += n * elem_bytes(d.dst_kind);
-        }
-        info.bytes_written += n * elem_bytes(d.dst_kind);
+        if (d.op != LIVER_OP_ZERO) plan.used[0][(size_t)d.src_rank * 4 + d.src_kind] = 1;
+        else info.pad_bytes += d.rows * d.run * elem_bytes(d.dst_kind);
         plan.used[1][(size_t)d.dst_rank * 4 + d.dst_kind] = 1;
     }
+    info.bytes_read = plan.direct.hbm_read;        // a piece that feeds a fused copy + cast is read once
+    info.bytes_written = plan.direct.hbm_written;
     for (uint8_t u : plan.used[0]) info.n_src_bufs_used += u;
     for (uint8_t u : plan.used[1]) info.n_dst_bufs_used += u;
     const uint64_t nd = plan.direct.dev.size(), np = plan.pack.dev.size(), nu = plan.unpack.dev.size();
@@ -540,64 +536,90 @@ int Builder::lower(List& list, bool staged) {
         return -1;
     };
     if (!staged) new_pass();
-    for (const liver_desc_t& d : list.pub) {
+    auto ref_a = [](const liver_desc_t& d) {
+        return BufRef{int8_t(d.src_rank < 0 ? 2 : 0), int8_t(d.src_rank < 0 ? 0 : d.src_kind), d.src_rank < 0 ? 0 : d.src_rank};
+    };
+    auto ref_b = [](const liver_desc_t& d) {
+        return BufRef{int8_t(d.dst_rank < 0 ? 2 : 1), int8_t(d.dst_rank < 0 ? 0 : d.dst_kind), d.dst_rank < 0 ? 0 : d.dst_rank};
+    };
+    auto add_buf = [&](Pass& p, BufRef r) {
+        int i = buf_index(p, r);
+        if (i < 0) {
+            i = (int)p.bufs.size();
+            p.bufs.push_back(r);
+        }
+        return (uint16_t)i;
+    };
+    for (size_t di = 0; di < list.pub.size(); ++di) {
+        const liver_desc_t& d = list.pub[di];
         if (staged && d.chunk != cur_chunk) {
             for (int c = cur_chunk + 1; c <= d.chunk; ++c) list.chunk_pass[c] = (uint32_t)list.passes.size();
             cur_chunk = d.chunk;
             new_pass();
         }
-        const bool zero = d.op == LIVER_OP_ZERO;
-        BufRef a{int8_t(d.src_rank < 0 ? 2 : 0), int8_t(d.src_rank < 0 ? 0 : d.src_kind), d.src_rank < 0 ? 0 : d.src_rank};
-        BufRef b{int8_t(d.dst_rank < 0 ? 2 : 1), int8_t(d.dst_rank < 0 ? 0 : d.dst_kind), d.dst_rank < 0 ? 0 : d.dst_rank};
-        {
-            Pass& p = list.passes.back();
-            int need = (zero || buf_index(p, a) >= 0 ? 0 : 1) + (buf_index(p, b) >= 0 ? 0 : 1);
-            if ((int)p.bufs.size() + need > MAX_PASS_BUFS) new_pass();
-        }
-        Pass& p = list.passes.back();
-        int ia = 0, ib;
-        if (!zero && (ia = buf_index(p, a)) < 0) {
-            ia = (int)p.bufs.size();
-            p.bufs.push_back(a);
-        }
-        if ((ib = buf_index(p, b)) < 0) {
-            ib = (int)p.bufs.size();
-            p.bufs.push_back(b);
-        }
-        // element sizes on each side
-        const i64 ea = zero ? 0 : elem_bytes(d.src_kind);  // the wire keeps the source type
+        const bool zero = d.op == LIVER_OP_ZERO, rows1 = d.rows == 1;
+        // element sizes on each side (the wire keeps the source type)
+        const i64 ea = zero ? 0 : elem_bytes(d.src_kind);
         const i64 eb = d.dst_rank < 0 ? ea : elem_bytes(d.dst_kind);
         DevDesc v{};
         v.a_off = (uint64_t)(d.src_off * ea);
         v.b_off = (uint64_t)(d.dst_off * eb);
-        const i64 a_stride = d.src_stride * ea, b_stride = d.dst_stride * eb;
-        const bool rows1 = d.rows == 1;
+        i64 a_stride = d.src_stride * ea, b_stride = d.dst_stride * eb, c_stride = 0;
+        const liver_desc_t* fused = nullptr;  // a CAST of the very same source piece that follows a COPY
+        if (d.op == LIVER_OP_COPY && ea == 4 && di + 1 < list.pub.size()) {
+            const liver_desc_t& n = list.pub[di + 1];
+            if (n.op == LIVER_OP_CAST_BF16 && n.chunk == d.chunk && n.src_rank == d.src_rank && n.src_kind == d.src_kind &&
+                n.src_off == d.src_off && n.src_stride == d.src_stride && n.rows == d.rows && n.run == d.run &&
+                v.a_off % 16 == 0 && v.b_off % 16 == 0 && (n.dst_off * 2) % 8 == 0 && d.run % 4 == 0 &&
+                (rows1 || (a_stride % 16 == 0 && b_stride % 16 == 0 && (n.dst_stride * 2) % 8 == 0)))
+                fused = &n;
+        }
+        {
+            Pass& p = list.passes.back();
+            int need = (zero || buf_index(p, ref_a(d)) >= 0 ? 0 : 1) + (buf_index(p, ref_b(d)) >= 0 ? 0 : 1) +
+                       (fused && buf_index(p, ref_b(*fused)) < 0 ? 1 : 0);
+            if ((int)p.bufs.size() + need > MAX_PASS_BUFS) new_pass();
+        }
+        Pass& p = list.passes.back();
+        v.a_buf = zero ? 0 : add_buf(p, ref_a(d));
+        v.b_buf = add_buf(p, ref_b(d));
         const bool al16 = v.a_off % 16 == 0 && v.b_off % 16 == 0 && (rows1 || (a_stride % 16 == 0 && b_stride % 16 == 0));
-        i64 run_units;
-        if (d.op == LIVER_OP_COPY) {
+        i64 run_units, a_unit, w_unit;  // bytes read / written per unit (for the traffic statistics)
+        if (fused) {
+            v.op = DOP_COPYCAST_V4, run_units = d.run / 4, a_unit = 16, w_unit = 24;
+            v.c_off = (uint64_t)(fused->dst_off * 2);
+            c_stride = fused->dst_stride * 2;
+            v.c_buf = add_buf(p, ref_b(*fused));
+            ++di;  // the CAST descriptor is covered
+        } else if (d.op == LIVER_OP_COPY) {
             if (ea != eb) {
                 why = "internal: copy between different element sizes";
                 return LIVER_E_UNSUPPORTED;
             }
-            if (al16 && (d.run * ea) % 16 == 0) v.op = DOP_COPY_V16, run_units = d.run * ea / 16;
-            else v.op = ea == 2 ? DOP_COPY_E2 : DOP_COPY_E4, run_units = d.run;
+            if (al16 && (d.run * ea) % 16 == 0) v.op = DOP_COPY_V16, run_units = d.run * ea / 16, a_unit = w_unit = 16;
+            else v.op = ea == 2 ? DOP_COPY_E2 : DOP_COPY_E4, run_units = d.run, a_unit = w_unit = ea;
         } else if (d.op == LIVER_OP_CAST_BF16) {
-            if (al16 && d.run % 8 == 0) v.op = DOP_CAST_V8, run_units = d.run / 8;
-            else v.op = DOP_CAST_E, run_units = d.run;
+            if (v.a_off % 16 == 0 && v.b_off % 8 == 0 && d.run % 4 == 0 && (rows1 || (a_stride % 16 == 0 && b_stride % 8 == 0))) {
+                v.op = DOP_CAST_V4, run_units = d.run / 4, a_unit = 16, w_unit = 8;
+                v.c_off = v.b_off, c_stride = b_stride, v.c_buf = v.b_buf;  // the bf16 target is the C operand
+            } else {
+                v.op = DOP_CAST_E, run_units = d.run, a_unit = 4, w_unit = 2;
+            }
         } else {
-            if (v.b_off % 16 == 0 && (d.run * eb) % 16 == 0) v.op = DOP_ZERO_V16, run_units = d.run * eb / 16;
-            else v.op = eb == 2 ? DOP_ZERO_E2 : DOP_ZERO_E4, run_units = d.run;
+            a_unit = 0;
+            if (v.b_off % 16 == 0 && (d.run * eb) % 16 == 0) v.op = DOP_ZERO_V16, run_units = d.run * eb / 16, w_unit = 16;
+            else v.op = eb == 2 ? DOP_ZERO_E2 : DOP_ZERO_E4, run_units = d.run, w_unit = eb;
         }
-        const i64 total = d.rows * run_units;
-        if (total <= 0 || total >= (i64(1) << 32) || (!rows1 && (a_stride >= (i64(1) << 32) || b_stride >= (i64(1) << 32)))) {
+        const i64 total = d.rows * run_units, lim = i64(1) << 32;
+        if (total <= 0 || total >= lim || (!rows1 && (a_stride >= lim || b_stride >= lim || c_stride >= lim))) {
             why = "internal: descriptor exceeds 32-bit unit counters";
             return LIVER_E_UNSUPPORTED;
         }
         v.a_stride = rows1 ? 0 : (uint32_t)a_stride;
         v.b_stride = rows1 ? 0 : (uint32_t)b_stride;
+        v.c_stride = rows1 ? 0 : (uint32_t)c_stride;
         v.run = rows1 ? (uint32_t)total : (uint32_t)run_units;
         v.total = (uint32_t)total;
-        v.a_buf = (uint16_t)ia, v.b_buf = (uint16_t)ib;
         const uint64_t tiles = ((uint64_t)total + TILE_UNITS - 1) / TILE_UNITS;
         if ((uint64_t)p.n_tiles + tiles >= (uint64_t(1) << 31)) {
             why = "internal: more than 2^31 tiles in one launch";
@@ -607,6 +629,8 @@ int Builder::lower(List& list, bool staged) {
         p.n_tiles += (uint32_t)tiles;
         p.desc_count += 1;
         list.dev.push_back(v);
+        list.hbm_read += total * a_unit;
+        list.hbm_written += total * w_unit;
     }
     if (staged)
         for (size_t c = (size_t)cur_chunk + 1; c <= n_chunks; ++c) list.chunk_pass[c] = (uint32_t)list.passes.size();

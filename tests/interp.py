@@ -108,3 +108,22 @@ def run_staged(plan, src_bufs, order=None):
 def used_dst(plan):
     n = lv.liver_plan_info(plan).n_dst_ranks
     return {(r, k) for r in range(n) for k in range(4) if lv.liver_plan_buffer_used(plan, 1, r, k)}
+
+
+def emulate_direct(plan, src_bufs):
+    """The LOWERED descriptors (what the kernels run) executed on host memory by the
+    library's bounds-checked emulator."""
+    dst, _ = alloc_dst(plan)
+    src = {k: np.ascontiguousarray(v) for k, v in src_bufs.items()}
+    lv.liver_debug_emulate_host(plan, lv.LIST_DIRECT, 0, src, dst, None)
+    return dst
+
+
+def emulate_staged(plan, src_bufs):
+    dst, _ = alloc_dst(plan)
+    src = {k: np.ascontiguousarray(v) for k, v in src_bufs.items()}
+    for c in range(lv.liver_plan_info(plan).n_chunks):
+        staging = np.full(plan.chunk_bytes, 0x3C, np.uint8)
+        lv.liver_debug_emulate_host(plan, lv.LIST_PACK, c, src, None, staging)
+        lv.liver_debug_emulate_host(plan, lv.LIST_UNPACK, c, None, dst, staging)
+    return dst
