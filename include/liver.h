@@ -171,7 +171,8 @@ int liver_plan_desc(const liver_plan_t* plan, int list, int64_t i, liver_desc_t*
 
 /* Launch shape of the copy kernels: grid_blocks workgroups of 256 threads
  * (0 = default: one per compute unit); tile_order 0 = each workgroup walks one
- * contiguous range of tiles (default), 1 = workgroups interleave tile by tile;
+ * contiguous range of tiles, 1 = workgroups interleave tile by tile, -1 =
+ * default (contiguous, except interleaved for direct launches below 48 GiB);
  * cache_hints bit 0 = non-temporal loads, bit 1 = non-temporal stores, -1 =
  * default (direct: both; pack: loads only; unpack: stores only, so that the
  * staging chunk may stay cache-resident).  Not thread-safe against concurrent
@@ -196,6 +197,18 @@ int liver_unpack(const liver_plan_t* plan, int chunk, const void* staging, void*
  * padding.  Equals pack + unpack over all chunks, bit for bit. */
 int liver_reshard(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs,
                   void* hip_stream);
+
+/* The whole staged reshard as a pipeline (the single-GPU analogue of Section 5:
+ * "the transfer is pipelined using isend() and irecv()"): chunk k is packed into
+ * staging[k % n_staging] on stream_pack while earlier chunks are unpacked on
+ * stream_unpack; events order pack(k) -> unpack(k) -> pack(k + n_staging).  Extra
+ * device memory is still O(B): n_staging chunks of chunk_bytes (1 <= n_staging <=
+ * 8; `staging` is a host array of device pointers).  The two streams may be the
+ * same.  Returns after enqueueing; all work has completed once stream_unpack has
+ * been synchronised.  Creates and destroys 2*n_staging HIP events per call (host
+ * objects; no device memory is allocated). */
+int liver_reshard_staged(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs,
+                         void* const* staging, int n_staging, void* stream_pack, void* stream_unpack);
 
 const char* liver_strerror(int code);
 

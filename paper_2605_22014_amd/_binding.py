@@ -125,6 +125,7 @@ def _load() -> C.CDLL:
     lib.liver_pack.argtypes = [P, C.c_int, C.POINTER(P), P, P]
     lib.liver_unpack.argtypes = [P, C.c_int, P, C.POINTER(P), P]
     lib.liver_reshard.argtypes = [P, C.POINTER(P), C.POINTER(P), P]
+    lib.liver_reshard_staged.argtypes = [P, C.POINTER(P), C.POINTER(P), C.POINTER(P), C.c_int, P, P]
     lib.liver_debug_emulate_host.argtypes = [P, C.c_int, C.c_int, C.POINTER(P), C.POINTER(P), P]
     lib.liver_strerror.argtypes = [C.c_int]
     lib.liver_strerror.restype = C.c_char_p
@@ -198,7 +199,7 @@ def liver_plan_desc(plan: Plan, which: int, i: int) -> Desc:
     return d
 
 
-def liver_plan_set_launch(plan: Plan, grid_blocks: int = 0, tile_order: int = 0, cache_hints: int = -1) -> None:
+def liver_plan_set_launch(plan: Plan, grid_blocks: int = 0, tile_order: int = -1, cache_hints: int = -1) -> None:
     _check(_lib.liver_plan_set_launch(plan.handle, grid_blocks, tile_order, cache_hints))
 
 
@@ -237,6 +238,13 @@ def liver_unpack(plan: Plan, chunk: int, staging, dst_bufs, stream=None) -> None
 def liver_reshard(plan: Plan, src_bufs, dst_bufs, stream=None) -> None:
     _check(_lib.liver_reshard(plan.handle, _table(src_bufs, plan.src.n_ranks), _table(dst_bufs, plan.dst.n_ranks),
                               _stream(stream)))
+
+
+def liver_reshard_staged(plan: Plan, src_bufs, dst_bufs, staging, stream_pack=None, stream_unpack=None) -> None:
+    """staging: list of device chunks (tensors or addresses) of chunk_bytes each."""
+    arr = (C.c_void_p * len(staging))(*[_addr(t) for t in staging])
+    _check(_lib.liver_reshard_staged(plan.handle, _table(src_bufs, plan.src.n_ranks), _table(dst_bufs, plan.dst.n_ranks),
+                                     arr, len(staging), _stream(stream_pack), _stream(stream_unpack)))
 
 
 def liver_debug_emulate_host(plan: Plan, which: int, chunk: int, src_bufs, dst_bufs, staging) -> None:

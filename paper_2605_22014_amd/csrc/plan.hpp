@@ -89,7 +89,7 @@ struct liver_plan {
     int device = -1;
     int n_cu = 0;
     // launch shape
-    int grid_blocks = 0, tile_order = 0, cache_hints = -1;  // 0 / -1 = library defaults
+    int grid_blocks = 0, tile_order = -1, cache_hints = -1;  // 0 / -1 / -1 = library defaults
 };
 
 namespace liver {

@@ -157,3 +157,48 @@ def test_errors_on_device():
     torch.cuda.synchronize()
     for k in keep:                                               # nothing written on error
         assert torch.equal(keep[k], dst_bufs[k])
+
+
+@pytest.mark.parametrize("n_staging,two_streams", [(1, False), (2, True), (3, True), (2, False)])
+def test_pipelined_staged_reshard(gpt2, n_staging, two_streams):
+    """liver_reshard_staged: pack(k+1) overlaps unpack(k) through n_staging chunks."""
+    cfg, spec, src, dst, world, want, dev = gpt2
+    print(f"gpt2_small pipelined n_staging {n_staging} two_streams {two_streams}", flush=True)
+    plan = _plan(spec, src, dst, 16 << 20)
+    out = alloc_dst(plan)
+    staging = [torch.empty(16 << 20, dtype=torch.uint8, device="cuda") for _ in range(n_staging)]
+    torch.cuda.synchronize()
+    if two_streams:
+        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+        lv.liver_reshard_staged(plan, dev, out, staging, sa, sb)
+        sb.synchronize()
+        sa.synchronize()
+    else:
+        lv.liver_reshard_staged(plan, dev, out, staging)
+        torch.cuda.synchronize()
+    check_against(out, want, plan, "pipelined staged")
+    with pytest.raises(lv.LiverError):
+        lv.liver_reshard_staged(plan, dev, out, [staging[0], staging[0]])
+
+
+def test_identity_layout_is_a_plain_copy():
+    """Same world on both sides: the target equals the source (with zero padding in the source)."""
+    cfg, spec, src, dst = cfg_objects("tiny_gpt")
+    print("identity layout", flush=True)
+    state = synth.logical_state(oracle.logical_tensors(spec), 5, "uniform")
+    world = make_world(spec, src, state, poison=False)
+    plan = _plan(spec, src, src, 1 << 20)
+    dev = to_dev(world)
+    check_against(run_direct(plan, dev), world, plan, "identity direct")
+    check_against(run_staged(plan, dev), world, plan, "identity staged")
+
+
+def test_round_trip_on_device():
+    """A -> B -> A on the GPU gives back A bit for bit (padding of B is zero, so it is a valid source)."""
+    cfg, spec, src, dst = cfg_objects("tiny_gpt")
+    print("round trip", flush=True)
+    state = synth.logical_state(oracle.logical_tensors(spec), 6, "uniform")
+    world = make_world(spec, src, state, poison=False)
+    there, back = _plan(spec, src, dst, 1 << 20), _plan(spec, dst, src, 1 << 20)
+    mid = run_direct(there, to_dev(world))
+    check_against(run_direct(back, mid), world, back, "A->B->A")

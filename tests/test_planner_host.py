@@ -241,3 +241,28 @@ def test_planner_at_paper_scale_is_subsecond():
         assert abs(params - 174.6e9) < 1e9
         assert info.stream_bytes > params * 12          # every fp32 element crosses once, bf16 once per replica
         assert best < 1.0, f"planning took {best:.2f} s"
+
+
+def test_pieces_above_2_30_elements_are_split():
+    """A 1.2 G-element embedding moves as one dense piece; the planner must cut it so
+    that the kernels' 32-bit unit counters cannot overflow, without gaps or overlap."""
+    spec = oracle.ModelSpec(n_layers=2, hidden=8192, n_q_heads=64, n_kv_heads=64, ffn=64, vocab=147456)
+    src, dst = oracle.Layout(1, 1, 1, 128), oracle.Layout(1, 2, 1, 128)
+    s, a, b = lv_objects(spec, src, dst)
+    plan = lv.liver_plan_create(s, a, b, 512 << 20)
+    info = lv.liver_plan_info(plan)
+    for which in (lv.LIST_DIRECT, lv.LIST_PACK, lv.LIST_UNPACK):
+        for rank in range(2):
+            sv = oracle.stage_view(spec, dst, 0, rank)
+            for kind in (0, 1):
+                if which == lv.LIST_PACK:
+                    continue
+                ivs = sorted((d.dst_off, d.rows * d.run) for d in descs(plan, which)
+                             if d.dst_rank == rank and d.dst_kind == kind and d.rows == 1)
+                pos = 0
+                for off, n in ivs:
+                    assert off == pos and 0 < n <= 1 << 30
+                    pos += n
+                assert pos == sv.n_local
+    assert max(d.rows * d.run for d in descs(plan, lv.LIST_DIRECT)) == 1 << 30
+    assert info.bytes_read == info.bytes_written == 14 * sum(oracle.stage_view(spec, dst, 0, pp).n_local for pp in range(2))
