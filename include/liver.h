@@ -44,7 +44,8 @@
  *     forward order (word/position embedding on the first stage; per layer ln1,
  *     qkv, o, ln2, fc1, fc2 with each bias after its weight; final norm and
  *     lm_head -- or a second copy of the tied word embedding if PP > 1 -- on the
- *     last stage); stage pp holds layers [pp*L/PP, (pp+1)*L/PP);
+ *     last stage); stage pp holds layers [pp*L/PP, (pp+1)*L/PP) (or, with an
+ *     interleaved schedule, vpp groups of L/(PP*vpp) layers: pp, pp+PP, ...);
  *   - the flat buffer is zero-padded to N_pad, a multiple of DP*pad_multiple
  *     elements.  LIVER_PARAM_BF16 holds all N_pad elements on every DP rank;
  *     LIVER_MASTER_F32 / LIVER_ADAM_M_F32 / LIVER_ADAM_V_F32 are split evenly:
@@ -104,6 +105,9 @@ typedef struct {
     uint32_t flags;                     /* target layout: LIVER_DERIVE_BF16.  Source layout: 0 */
     uint32_t kind_mask;                 /* target layout: bit k set = buffer kind k takes part;
                                            0 = all four.  Source layout: 0 */
+    int32_t vpp;                        /* model chunks per pipeline stage (interleaved schedule);
+                                           0 or 1 = none.  The layers are cut into pp*vpp groups and
+                                           stage p holds groups p, p+pp, p+2*pp, ... in that order */
 } liver_layout_t;
 
 typedef struct {
@@ -146,7 +150,7 @@ typedef struct {
  * not, the plan is host-only: it can be inspected but pack / unpack / reshard
  * return LIVER_E_NO_DEVICE.
  * Errors: INVALID_ARG (null pointer, bad chunk_bytes, non-positive dimension),
- * UNSUPPORTED (n_layers % pp, hidden % n_q_heads, n_q_heads % n_kv_heads,
+ * UNSUPPORTED (n_layers % (pp*vpp), hidden % n_q_heads, n_q_heads % n_kv_heads,
  * n_kv_heads % tp, ffn % tp or vocab % tp non-zero on either side; only_* out of
  * range or set on the source layout), NOMEM, HIP. */
 int liver_plan_create(const liver_model_spec_t* spec, const liver_layout_t* src,

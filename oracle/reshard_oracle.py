@@ -37,7 +37,11 @@ Megatron-style mixed-parallel training, stated so a reader can check it by eye):
       read is the one with the lowest coordinate (dp=0, tp=0, first stage).
   R8  with tied embeddings and PP>1 the last stage holds a second physical copy
       of the word embedding (same TP split) after the final norm.
-  R9  stage pp owns layers [pp*L/PP, (pp+1)*L/PP).
+  R9  stage pp owns layers [pp*L/PP, (pp+1)*L/PP).  With an interleaved schedule
+      (vpp > 1 model chunks per stage, as in the interleaved 1F1B the paper's
+      Section 4.7 mentions) the layers are cut into PP*vpp groups of c layers and
+      stage pp owns groups pp, pp+PP, pp+2*PP, ...; they sit in its flat buffer in
+      that order.  Embeddings stay on stage 0, final norm / head on stage PP-1.
   R10 fp32 -> bf16 is round-to-nearest-even on the upper 16 bits; NaN keeps sign
       and upper payload and gets the quiet bit.
   R12 buffer-table index of a rank is tp + TP*(dp + DP*pp).
@@ -83,6 +87,7 @@ class Layout:
     pp: int
     dp: int
     pad_multiple: int = 128
+    vpp: int = 1              # R9b: model chunks per stage (interleaved pipeline schedule)
 
     @property
     def n_ranks(self) -> int:
@@ -93,7 +98,7 @@ class Layout:
 
 
 def check_supported(spec: ModelSpec, lay: Layout) -> None:
-    ok = (spec.n_layers % lay.pp == 0 and spec.hidden % spec.n_q_heads == 0
+    ok = (lay.vpp >= 1 and spec.n_layers % (lay.pp * lay.vpp) == 0 and spec.hidden % spec.n_q_heads == 0
           and spec.n_q_heads % spec.n_kv_heads == 0 and spec.n_kv_heads % lay.tp == 0
           and spec.ffn % lay.tp == 0 and spec.vocab % lay.tp == 0
           and min(lay.tp, lay.pp, lay.dp, lay.pad_multiple) >= 1)
@@ -183,6 +188,12 @@ def _cols(a: int, b: int) -> Tuple[slice, ...]:
 _ALL: Tuple[slice, ...] = (slice(None),)
 
 
+def stage_layers(spec: ModelSpec, lay: Layout, pp: int) -> List[int]:
+    """Layers held by stage pp, in the order they sit in its flat buffer (R9)."""
+    c = spec.n_layers // (lay.pp * lay.vpp)          # layers per model chunk
+    return [l for v in range(lay.vpp) for l in range((v * lay.pp + pp) * c, (v * lay.pp + pp + 1) * c)]
+
+
 def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int) -> StageView:
     """Ordered physical parameters of rank column (tp, pp) -- R2..R5, R8, R9."""
     check_supported(spec, lay)
@@ -229,12 +240,11 @@ def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int) -> StageView:
                               Block(p + "up." + suffix, _rows(tp * n, (tp + 1) * n), _rows(n, 2 * n))],
                              True))
 
-    per_stage = spec.n_layers // lay.pp              # R9
     if pp == 0:
         split0("embed.word", "embed.word")
         if spec.max_pos:
             replicated("embed.pos")
-    for l in range(pp * per_stage, (pp + 1) * per_stage):
+    for l in stage_layers(spec, lay, pp):
         p = f"L{l}."
         replicated(p + "ln1.w")
         if spec.norm_bias:
@@ -409,6 +419,6 @@ def expected_shards(spec: ModelSpec, lay: Layout, logical: Dict[str, np.ndarray]
 
 
 __all__ = ["PARAM", "MASTER", "ADAM_M", "ADAM_V", "KINDS", "WORD", "ModelSpec", "Layout",
-           "check_supported", "logical_tensors", "Block", "PhysParam", "StageView", "stage_view",
+           "check_supported", "logical_tensors", "Block", "PhysParam", "StageView", "stage_layers", "stage_view",
            "buffer_elems", "Reader", "dict_reader", "read_flat", "gather_logical", "build_shard",
            "split_logical", "rne_bf16", "reshard_state", "expected_shards"]

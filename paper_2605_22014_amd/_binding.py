@@ -44,7 +44,7 @@ class _Spec(C.Structure):
 
 class _Layout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("tp", "pp", "dp", "pad_multiple", "only_tp", "only_pp", "only_dp")] \
-        + [("flags", C.c_uint32), ("kind_mask", C.c_uint32)]
+        + [("flags", C.c_uint32), ("kind_mask", C.c_uint32), ("vpp", C.c_int32)]
 
 
 class PlanInfo(C.Structure):
@@ -91,6 +91,7 @@ class Layout:
     only_dp: int = -1
     derive_bf16: bool = False
     kinds: Optional[Tuple[int, ...]] = None      # None = all four
+    vpp: int = 1                                 # model chunks per stage (interleaved pipeline)
 
     @property
     def n_ranks(self) -> int:
@@ -102,7 +103,7 @@ class Layout:
     def _c(self) -> _Layout:
         mask = 0 if self.kinds is None else sum(1 << k for k in set(self.kinds))
         return _Layout(self.tp, self.pp, self.dp, self.pad_multiple, self.only_tp, self.only_pp, self.only_dp,
-                       _DERIVE * self.derive_bf16, mask)
+                       _DERIVE * self.derive_bf16, mask, self.vpp)
 
 
 def _load() -> C.CDLL:

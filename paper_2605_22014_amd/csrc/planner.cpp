@@ -49,7 +49,7 @@ struct Column {
 };
 
 // Physical parameter order and shapes of rank column (tp, pp).
-Column build_column(const Geo& g, int TP, int PP, int tp, int pp) {
+Column build_column(const Geo& g, int TP, int PP, int VPP, int tp, int pp) {
     Column col;
     col.tp = tp;
     col.pp = pp;
@@ -65,8 +65,9 @@ Column build_column(const Geo& g, int TP, int PP, int tp, int pp) {
         add(T_EMBED_WORD, 0, tp * vn, (tp + 1) * vn, 0, g.H, true);
         if (g.P) add(T_EMBED_POS, 0, 0, g.P, 0, g.H, lead);
     }
-    const i64 per = g.L / PP;
-    for (i64 l = pp * per; l < (pp + 1) * per; ++l) {
+    const i64 per = g.L / ((i64)PP * VPP);  // layers per model chunk; stage pp holds chunks pp, pp+PP, ...
+    for (i64 li = 0; li < per * VPP; ++li) {
+        const i64 l = ((li / per) * PP + pp) * per + li % per;
         const int slot = 1 + (int)l;
         const int b = T_GLOBALS + (int)l * T_PER_LAYER;
         add(b + LN1_W, slot, 0, 1, 0, g.H, lead);
@@ -123,6 +124,7 @@ struct Entry {
 };
 
 inline int elem_bytes(int kind) { return kind == LIVER_PARAM_BF16 ? 2 : 4; }
+inline int vpp_of(const liver_layout_t& l) { return l.vpp > 1 ? l.vpp : 1; }
 
 // Payload elements [p0, p1) of `e` (row-major over rows x run) as up to three
 // pieces: the tail of a row, whole rows, the head of a row.
@@ -295,8 +297,8 @@ int Builder::run() {
         return LIVER_E_INVALID_ARG;
     }
     for (const liver_layout_t* l : {&S, &D})
-        if (l->tp <= 0 || l->pp <= 0 || l->dp <= 0 || l->pad_multiple <= 0) {
-            why = "layout: tp, pp, dp, pad_multiple must be positive";
+        if (l->tp <= 0 || l->pp <= 0 || l->dp <= 0 || l->pad_multiple <= 0 || l->vpp < 0) {
+            why = "layout: tp, pp, dp, pad_multiple must be positive, vpp non-negative";
             return LIVER_E_INVALID_ARG;
         }
     if (plan.chunk_bytes < 256 || plan.chunk_bytes % 256) {
@@ -308,8 +310,8 @@ int Builder::run() {
         return LIVER_E_UNSUPPORTED;
     }
     for (const liver_layout_t* l : {&S, &D})
-        if (sp.n_layers % l->pp || sp.n_kv_heads % l->tp || sp.ffn % l->tp || sp.vocab % l->tp) {
-            why = "n_layers % pp, n_kv_heads % tp, ffn % tp or vocab % tp != 0";
+        if (sp.n_layers % (l->pp * vpp_of(*l)) || sp.n_kv_heads % l->tp || sp.ffn % l->tp || sp.vocab % l->tp) {
+            why = "n_layers % (pp*vpp), n_kv_heads % tp, ffn % tp or vocab % tp != 0";
             return LIVER_E_UNSUPPORTED;
         }
     if (S.only_tp != -1 || S.only_pp != -1 || S.only_dp != -1 || S.flags || S.kind_mask) {
@@ -337,7 +339,7 @@ int Builder::run() {
         const i64 quantum = (i64)lay.dp * lay.pad_multiple;
         for (int pp = 0; pp < lay.pp; ++pp) {
             StageSize s;
-            s.n_local = build_column(g, lay.tp, lay.pp, 0, pp).n_local;
+            s.n_local = build_column(g, lay.tp, lay.pp, vpp_of(lay), 0, pp).n_local;
             s.n_pad = (s.n_local + quantum - 1) / quantum * quantum;
             s.S = s.n_pad / lay.dp;
             out[pp] = s;
@@ -354,7 +356,7 @@ int Builder::run() {
     std::vector<std::vector<SrcRect>> by_tensor(n_tensors);  // pruning: only views of the same tensor meet
     for (int pp = 0; pp < S.pp; ++pp)
         for (int tp = 0; tp < S.tp; ++tp) {
-            Column c = build_column(g, S.tp, S.pp, tp, pp);
+            Column c = build_column(g, S.tp, S.pp, vpp_of(S), tp, pp);
             for (const Rect& r : c.rects)
                 if (r.canonical) by_tensor[r.tensor].push_back({r, tp, pp});
         }
@@ -368,7 +370,7 @@ int Builder::run() {
         if (D.only_pp >= 0 && D.only_pp != pp) continue;
         for (int tp = 0; tp < D.tp; ++tp) {
             if (D.only_tp >= 0 && D.only_tp != tp) continue;
-            Column col = build_column(g, D.tp, D.pp, tp, pp);
+            Column col = build_column(g, D.tp, D.pp, vpp_of(D), tp, pp);
             std::vector<Piece> pieces;
             for (const Rect& d : col.rects) {
                 const i64 dw = d.c1 - d.c0;

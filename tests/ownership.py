@@ -43,16 +43,18 @@ def layer_param_sizes(spec, TP, l):
     return out
 
 
-def stage_param_sizes(spec, TP, PP, pp):
+def stage_param_sizes(spec, TP, PP, pp, vpp=1):
     H, hd, Q, KV, F, V = dims(spec)
     out = []
     if pp == 0:
         out.append(("embed.word", V * H // TP))
         if spec.max_pos:
             out.append(("embed.pos", spec.max_pos * H))
-    per = spec.n_layers // PP
-    for l in range(pp * per, (pp + 1) * per):
-        out += layer_param_sizes(spec, TP, l)
+    c = spec.n_layers // (PP * vpp)         # layers per model chunk; stage pp holds chunks pp, pp+PP, ...
+    for v in range(vpp):
+        first = (v * PP + pp) * c
+        for l in range(first, first + c):
+            out += layer_param_sizes(spec, TP, l)
     if pp == PP - 1:
         out.append(("final_norm.w", H))
         if spec.norm_bias:
@@ -64,13 +66,13 @@ def stage_param_sizes(spec, TP, PP, pp):
     return out
 
 
-def n_local(spec, TP, PP, pp):
-    return sum(n for _, n in stage_param_sizes(spec, TP, PP, pp))
+def n_local(spec, TP, PP, pp, vpp=1):
+    return sum(n for _, n in stage_param_sizes(spec, TP, PP, pp, vpp))
 
 
-def n_pad(spec, TP, PP, DP, pad_multiple, pp):
+def n_pad(spec, TP, PP, DP, pad_multiple, pp, vpp=1):
     q = DP * pad_multiple
-    return (n_local(spec, TP, PP, pp) + q - 1) // q * q
+    return (n_local(spec, TP, PP, pp, vpp) + q - 1) // q * q
 
 
 def owner(spec, TP, tp, phys, k):
@@ -130,13 +132,13 @@ def owner(spec, TP, tp, phys, k):
     raise KeyError(phys)
 
 
-def column_ownership(spec, TP, PP, tp, pp):
+def column_ownership(spec, TP, PP, tp, pp, vpp=1):
     """For flat offsets 0..N_local-1 of rank column (tp, pp): (names, idx, canonical).
 
     canonical[k] is False where the element is a replica that a gather must not
     read: TP-replicated parameters on tp > 0 and the tied-embedding copy."""
     names, idx, canon = [], [], []
-    for phys, n in stage_param_sizes(spec, TP, PP, pp):
+    for phys, n in stage_param_sizes(spec, TP, PP, pp, vpp):
         nm, ix = owner(spec, TP, tp, phys, np.arange(n, dtype=np.int64))
         names.append(nm)
         idx.append(ix)

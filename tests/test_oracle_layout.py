@@ -22,18 +22,19 @@ SPECS = {
     "mqa_tied": oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=4, n_kv_heads=1, ffn=64, vocab=32,
                                  tied_embed=True),
 }
-LAYOUTS = [(1, 1, 1, 128), (2, 1, 2, 128), (1, 2, 2, 128), (2, 2, 3, 4), (4, 2, 1, 1), (2, 1, 3, 1)]
+LAYOUTS = [(1, 1, 1, 128), (2, 1, 2, 128), (1, 2, 2, 128), (2, 2, 3, 4), (4, 2, 1, 1), (2, 1, 3, 1),
+           (2, 2, 2, 4, 2), (1, 1, 1, 1, 2), (1, 2, 3, 1, 1)]       # 5th entry: vpp (interleaved stages)
 
 
 def _cases():
     for sname, spec in SPECS.items():
-        for (tp, pp, dp, pm) in LAYOUTS:
-            lay = oracle.Layout(tp, pp, dp, pm)
+        for (tp, pp, dp, pm, *rest) in LAYOUTS:
+            lay = oracle.Layout(tp, pp, dp, pm, *rest)
             try:
                 oracle.check_supported(spec, lay)
             except ValueError:
                 continue
-            yield pytest.param(spec, lay, id=f"{sname}-tp{tp}pp{pp}dp{dp}pm{pm}")
+            yield pytest.param(spec, lay, id=f"{sname}-tp{tp}pp{pp}dp{dp}pm{pm}v{lay.vpp}")
 
 
 def _tensor_ordinal_state(spec):
@@ -53,10 +54,10 @@ def test_split_matches_ownership(spec, lay):
     w_hi = make_world(spec, lay, synth.index_encoded_state(shapes, half=1), poison=False)
     w_ord = make_world(spec, lay, _tensor_ordinal_state(spec), poison=False)
     for pp in range(lay.pp):
-        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp)
+        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp)
         S = npad // lay.dp
         for tp in range(lay.tp):
-            names, idx, _ = own.column_ownership(spec, lay.tp, lay.pp, tp, pp)
+            names, idx, _ = own.column_ownership(spec, lay.tp, lay.pp, tp, pp, lay.vpp)
             nl = len(names)
             exp_idx = np.zeros(npad, np.int64)
             exp_idx[:nl] = idx
@@ -116,3 +117,18 @@ def test_gather_detects_broken_tiling(monkeypatch):
     monkeypatch.setattr(oracle.reshard_oracle, "stage_view", broken)
     with pytest.raises(AssertionError):
         oracle.gather_logical(spec, lay, oracle.MASTER, oracle.dict_reader(world))
+
+
+def test_interleaved_stage_layers():
+    """Interleaved schedule: L=8, PP=2, vpp=2 -> stage 0 holds layers 0,1,4,5 and stage 1 holds 2,3,6,7,
+    in that order in the flat buffer; vpp=1 is the plain even split."""
+    spec = oracle.ModelSpec(n_layers=8, hidden=32, n_q_heads=4, n_kv_heads=4, ffn=64, vocab=32)
+    assert oracle.stage_layers(spec, oracle.Layout(1, 2, 1, 1, 2), 0) == [0, 1, 4, 5]
+    assert oracle.stage_layers(spec, oracle.Layout(1, 2, 1, 1, 2), 1) == [2, 3, 6, 7]
+    assert oracle.stage_layers(spec, oracle.Layout(1, 4, 1, 1, 2), 3) == [3, 7]
+    assert oracle.stage_layers(spec, oracle.Layout(1, 2, 1, 1, 1), 1) == [4, 5, 6, 7]
+    sv = oracle.stage_view(spec, oracle.Layout(1, 2, 1, 1, 2), 0, 1)
+    order = [p.name.split(".")[0] for p in sv.params if p.name.endswith("ln1.w")]
+    assert order == ["L2", "L3", "L6", "L7"]
+    with pytest.raises(ValueError):
+        oracle.stage_view(spec, oracle.Layout(1, 4, 1, 1, 4), 0, 0)

@@ -26,6 +26,8 @@ BRUTE = [
     (ODD6, (6, 1, 1, 4), (2, 3, 2, 1)),
     (ODD6, (3, 2, 3, 1), (6, 6, 1, 1)),
     (ODD6, (2, 3, 2, 1), (1, 1, 3, 4)),
+    (ODD6, (2, 3, 2, 1, 2), (3, 1, 1, 4, 3)),        # interleaved stages: vpp 2 -> vpp 3
+    (ODD6, (1, 2, 1, 4), (2, 3, 2, 1, 2)),           # plain split -> interleaved
 ]
 
 

@@ -20,8 +20,8 @@ def poison_pads(spec, lay, bufs):
     """Overwrite the padding of every buffer of world `lay` with NaN sentinels
     (source padding must never be read by a reshard)."""
     for pp in range(lay.pp):
-        nl = own.n_local(spec, lay.tp, lay.pp, pp)
-        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp)
+        nl = own.n_local(spec, lay.tp, lay.pp, pp, lay.vpp)
+        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp)
         S = npad // lay.dp
         for tp in range(lay.tp):
             for dp in range(lay.dp):
@@ -48,10 +48,10 @@ def corrupt_replicas(spec, lay, bufs):
     formulas (not by the oracle): TP-replicated parameters on tp > 0, the tied
     embedding copy, and PARAM replicas with dp > 0."""
     for pp in range(lay.pp):
-        nl = own.n_local(spec, lay.tp, lay.pp, pp)
-        S = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp) // lay.dp
+        nl = own.n_local(spec, lay.tp, lay.pp, pp, lay.vpp)
+        S = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp) // lay.dp
         for tp in range(lay.tp):
-            _, _, canon = own.column_ownership(spec, lay.tp, lay.pp, tp, pp)
+            _, _, canon = own.column_ownership(spec, lay.tp, lay.pp, tp, pp, lay.vpp)
             bad = np.flatnonzero(~canon)
             for dp in range(lay.dp):
                 r = lay.rank(tp, pp, dp)
@@ -81,10 +81,10 @@ def brute_reshard(spec, src, dst, src_bufs, derive=False):
     alone (tiny models only).  Independent of the oracle's slicing."""
     value = {k: {} for k in oracle.KINDS}
     for pp in range(src.pp):
-        npad = own.n_pad(spec, src.tp, src.pp, src.dp, src.pad_multiple, pp)
+        npad = own.n_pad(spec, src.tp, src.pp, src.dp, src.pad_multiple, pp, src.vpp)
         S = npad // src.dp
         for tp in range(src.tp):
-            names, idx, canon = own.column_ownership(spec, src.tp, src.pp, tp, pp)
+            names, idx, canon = own.column_ownership(spec, src.tp, src.pp, tp, pp, src.vpp)
             for k in range(len(names)):
                 if not canon[k]:
                     continue
@@ -98,10 +98,10 @@ def brute_reshard(spec, src, dst, src_bufs, derive=False):
         value[oracle.PARAM] = {key: _rne_scalar(int(v)) for key, v in value[oracle.MASTER].items()}
     out = {}
     for pp in range(dst.pp):
-        npad = own.n_pad(spec, dst.tp, dst.pp, dst.dp, dst.pad_multiple, pp)
+        npad = own.n_pad(spec, dst.tp, dst.pp, dst.dp, dst.pad_multiple, pp, dst.vpp)
         S = npad // dst.dp
         for tp in range(dst.tp):
-            names, idx, _ = own.column_ownership(spec, dst.tp, dst.pp, tp, pp)
+            names, idx, _ = own.column_ownership(spec, dst.tp, dst.pp, tp, pp, dst.vpp)
             flat = {kind: np.zeros(npad, oracle.WORD[kind]) for kind in oracle.KINDS}
             for k in range(len(names)):
                 key = (names[k], int(idx[k]))
