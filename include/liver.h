@@ -38,7 +38,9 @@
  *     linears are replicated over TP;
  *   - q, k, v are one fused parameter per rank, grouped per kv-head group:
  *     [q rows of group g ; k rows of g ; v rows of g] for the rank's groups in
- *     ascending order; gated FFNs store [gate rows of the rank ; up rows of the
+ *     ascending order (if TP > n_kv_heads, group g is replicated on the TP/n_kv
+ *     ranks g*r..g*r+r-1: rank g*r+j holds the j-th part of the group's q rows,
+ *     then all of k, then all of v; k and v are read from j = 0); gated FFNs store [gate rows of the rank ; up rows of the
  *     rank] as one parameter;
  *   - a (tp, pp) rank's parameters are flattened and packed back to back in
  *     forward order (word/position embedding on the first stage; per layer ln1,
@@ -151,7 +153,8 @@ typedef struct {
  * return LIVER_E_NO_DEVICE.
  * Errors: INVALID_ARG (null pointer, bad chunk_bytes, non-positive dimension),
  * UNSUPPORTED (n_layers % (pp*vpp), hidden % n_q_heads, n_q_heads % n_kv_heads,
- * n_kv_heads % tp, ffn % tp or vocab % tp non-zero on either side; only_* out of
+ * ffn % tp or vocab % tp non-zero, kv heads neither split (n_kv_heads % tp == 0) nor
+ * replicated evenly (tp % n_kv_heads == 0 and q heads per group % (tp/n_kv_heads) == 0); only_* out of
  * range or set on the source layout), NOMEM, HIP. */
 int liver_plan_create(const liver_model_spec_t* spec, const liver_layout_t* src,
                       const liver_layout_t* dst, size_t chunk_bytes, liver_plan_t** out);

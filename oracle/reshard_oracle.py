@@ -25,6 +25,10 @@ Megatron-style mixed-parallel training, stated so a reader can check it by eye):
   R3  q, k, v live in ONE fused physical parameter per rank, grouped per
       kv-head group g: [q rows of the group ; k rows of g ; v rows of g], groups
       in ascending order (MHA: per head [q_h; k_h; v_h]).
+  R3b if TP > n_kv (TP a multiple of n_kv), kv group g is REPLICATED on the
+      r = TP/n_kv ranks g*r .. g*r+r-1; rank g*r+j holds the j-th r-th of the
+      group's q rows, then all k rows of g, then all v rows of g.  A gather reads
+      k and v from the rank with j = 0.
   R4  with a gated FFN, gate and up live in one physical parameter per rank as
       [gate rows of this rank ; up rows of this rank].
   R5  a (tp, pp) rank's parameters are flattened row-major and packed back to
@@ -97,9 +101,17 @@ class Layout:
         return tp + self.tp * (dp + self.dp * pp)
 
 
+def _kv_split_ok(spec: ModelSpec, tp: int) -> bool:
+    """kv groups split evenly over TP, or (R3b) each kv group replicated over TP/n_kv ranks."""
+    if spec.n_kv_heads % tp == 0:
+        return True
+    r = tp // spec.n_kv_heads
+    return tp % spec.n_kv_heads == 0 and (spec.n_q_heads // spec.n_kv_heads) % r == 0
+
+
 def check_supported(spec: ModelSpec, lay: Layout) -> None:
     ok = (lay.vpp >= 1 and spec.n_layers % (lay.pp * lay.vpp) == 0 and spec.hidden % spec.n_q_heads == 0
-          and spec.n_q_heads % spec.n_kv_heads == 0 and spec.n_kv_heads % lay.tp == 0
+          and spec.n_q_heads % spec.n_kv_heads == 0 and _kv_split_ok(spec, lay.tp)
           and spec.ffn % lay.tp == 0 and spec.vocab % lay.tp == 0
           and min(lay.tp, lay.pp, lay.dp, lay.pad_multiple) >= 1)
     if not ok:
@@ -150,10 +162,12 @@ def logical_tensors(spec: ModelSpec) -> Dict[str, Tuple[int, ...]]:
 # ------------------------------------------------------------- physical params
 @dataclass(frozen=True)
 class Block:
-    """local[loc] holds logical[name][idx] (tuples of slices)."""
+    """local[loc] holds logical[name][idx] (tuples of slices).  canonical: may a
+    gather read this block from this rank (R7)?"""
     name: str
     idx: Tuple[slice, ...]
     loc: Tuple[slice, ...]
+    canonical: bool = True
 
 
 @dataclass
@@ -220,6 +234,14 @@ def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int) -> StageView:
     def fused_qkv(p: str, suffix: str) -> None:      # R3
         tail = shapes[p + "q." + suffix][1:]
         blocks, row = [], 0
+        if g_loc == 0:                               # R3b: TP > n_kv, kv group replicated on r ranks
+            r = TP // spec.n_kv_heads
+            g, j, nq = tp // r, tp % r, (qpg // r) * hd
+            for nm, lo, n, canon in ((p + "q." + suffix, g * qpg * hd + j * nq, nq, True),
+                                     (p + "k." + suffix, g * hd, hd, j == 0),
+                                     (p + "v." + suffix, g * hd, hd, j == 0)):
+                blocks.append(Block(nm, _rows(lo, lo + n), _rows(row, row + n), canon))
+                row += n
         for j in range(g_loc):
             g = tp * g_loc + j
             for nm, lo, n in ((p + "q." + suffix, g * qpg * hd, qpg * hd),
@@ -328,12 +350,12 @@ def gather_logical(spec: ModelSpec, lay: Layout, kind: int, read: Reader,
         for tp in range(lay.tp):
             sv = stage_view(spec, lay, tp, pp)
             for prm in sv.params:
-                if not prm.canonical or not any(b.name in want for b in prm.blocks):
+                if not prm.canonical or not any(b.name in want and b.canonical for b in prm.blocks):
                     continue
                 local = read_flat(read, lay, tp, pp, kind, prm.offset, prm.offset + prm.size,
                                   sv.S).reshape(prm.shape)
                 for b in prm.blocks:
-                    if b.name in want:
+                    if b.name in want and b.canonical:
                         logical[b.name][b.idx] = local[b.loc]
                         if hits is not None:
                             hits[b.name][b.idx] += 1

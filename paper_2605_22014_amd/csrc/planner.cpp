@@ -72,6 +72,20 @@ Column build_column(const Geo& g, int TP, int PP, int VPP, int tp, int pp) {
         const int b = T_GLOBALS + (int)l * T_PER_LAYER;
         add(b + LN1_W, slot, 0, 1, 0, g.H, lead);
         if (g.norm_bias) add(b + LN1_B, slot, 0, 1, 0, g.H, lead);
+        // TP > n_kv: kv group gi is replicated on rep = TP/n_kv ranks; this rank holds its part of the
+        // group's q rows and a full copy of k and v (read from the rank holding part 0)
+        const i64 rep = g_loc == 0 ? TP / g.nkv : 1, part = tp % rep, nq = g.qpg / rep * g.hd;
+        if (g_loc == 0) {
+            const i64 gi = tp / rep;
+            add(b + Q_W, slot, gi * g.qpg * g.hd + part * nq, gi * g.qpg * g.hd + (part + 1) * nq, 0, g.H, true);
+            add(b + K_W, slot, gi * g.hd, (gi + 1) * g.hd, 0, g.H, part == 0);
+            add(b + V_W, slot, gi * g.hd, (gi + 1) * g.hd, 0, g.H, part == 0);
+            if (g.lin_bias) {
+                add(b + Q_B, slot, 0, 1, gi * g.qpg * g.hd + part * nq, gi * g.qpg * g.hd + (part + 1) * nq, true);
+                add(b + K_B, slot, 0, 1, gi * g.hd, (gi + 1) * g.hd, part == 0);
+                add(b + V_B, slot, 0, 1, gi * g.hd, (gi + 1) * g.hd, part == 0);
+            }
+        }
         for (i64 j = 0; j < g_loc; ++j) {  // fused qkv weight: [q of group ; k ; v] per kv group
             const i64 gi = tp * g_loc + j;
             add(b + Q_W, slot, gi * g.qpg * g.hd, (gi + 1) * g.qpg * g.hd, 0, g.H, true);
@@ -309,11 +323,14 @@ int Builder::run() {
         why = "hidden % n_q_heads or n_q_heads % n_kv_heads != 0";
         return LIVER_E_UNSUPPORTED;
     }
-    for (const liver_layout_t* l : {&S, &D})
-        if (sp.n_layers % (l->pp * vpp_of(*l)) || sp.n_kv_heads % l->tp || sp.ffn % l->tp || sp.vocab % l->tp) {
-            why = "n_layers % (pp*vpp), n_kv_heads % tp, ffn % tp or vocab % tp != 0";
+    for (const liver_layout_t* l : {&S, &D}) {
+        const bool kv_ok = sp.n_kv_heads % l->tp == 0 ||
+                           (l->tp % sp.n_kv_heads == 0 && (sp.n_q_heads / sp.n_kv_heads) % (l->tp / sp.n_kv_heads) == 0);
+        if (sp.n_layers % (l->pp * vpp_of(*l)) || !kv_ok || sp.ffn % l->tp || sp.vocab % l->tp) {
+            why = "n_layers % (pp*vpp), ffn % tp or vocab % tp != 0, or kv heads neither split nor replicated evenly over tp";
             return LIVER_E_UNSUPPORTED;
         }
+    }
     if (S.only_tp != -1 || S.only_pp != -1 || S.only_dp != -1 || S.flags || S.kind_mask) {
         why = "source layout: only_* must be -1, flags and kind_mask 0";
         return LIVER_E_UNSUPPORTED;

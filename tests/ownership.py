@@ -24,9 +24,11 @@ def layer_param_sizes(spec, TP, l):
     out = [(p + "ln1.w", H)]
     if spec.norm_bias:
         out.append((p + "ln1.b", H))
-    out.append((p + "qkv.w", (Q + 2 * KV) * H // TP))
+    # kv groups split over TP; if TP > n_kv every rank holds Q/TP q rows plus ONE whole k and v head
+    qkv_rows = (Q + 2 * KV) // TP if spec.n_kv_heads % TP == 0 else Q // TP + 2 * hd
+    out.append((p + "qkv.w", qkv_rows * H))
     if spec.linear_bias:
-        out.append((p + "qkv.b", (Q + 2 * KV) // TP))
+        out.append((p + "qkv.b", qkv_rows))
     out.append((p + "o.w", H * Q // TP))
     if spec.linear_bias:
         out.append((p + "o.b", H))
@@ -106,6 +108,15 @@ def owner(spec, TP, tp, phys, k):
         qpg = spec.n_q_heads // spec.n_kv_heads
         g_loc = spec.n_kv_heads // TP
         i, j = k // C, k % C
+        if g_loc == 0:                      # kv group g replicated on r = TP/n_kv ranks; this is its part `part`
+            r = TP // spec.n_kv_heads
+            g, part, nq = tp // r, tp % r, (qpg // r) * hd
+            is_q, is_k = i < nq, (i >= nq) & (i < nq + hd)
+            row = np.where(is_q, g * qpg * hd + part * nq + i, np.where(is_k, g * hd + (i - nq), g * hd + (i - nq - hd)))
+            names[:] = pre + "v." + sfx
+            names[is_k] = pre + "k." + sfx
+            names[is_q] = pre + "q." + sfx
+            return names, row * C + j
         G = (qpg + 2) * hd
         g = tp * g_loc + i // G
         w = i % G
@@ -145,6 +156,8 @@ def column_ownership(spec, TP, PP, tp, pp, vpp=1):
         leaf = phys.split(".", 1)[1] if phys.startswith("L") else phys
         replicated = leaf in ("ln1.w", "ln1.b", "ln2.w", "ln2.b", "o.b", "down.b", "final_norm.w",
                               "final_norm.b", "embed.pos")
-        ok = not (replicated and tp > 0) and "(tied copy)" not in phys
-        canon.append(np.full(n, ok))
+        ok = np.full(n, not (replicated and tp > 0) and "(tied copy)" not in phys)
+        if leaf in ("qkv.w", "qkv.b") and spec.n_kv_heads % TP and tp % (TP // spec.n_kv_heads):
+            ok &= np.char.endswith(nm.astype(str), ("q." + leaf[-1]))      # replicated k / v: read from part 0 only
+        canon.append(ok)
     return np.concatenate(names), np.concatenate(idx), np.concatenate(canon)

@@ -19,11 +19,14 @@ SPECS = {
     "gqa_glu_bias_untied": oracle.ModelSpec(n_layers=2, hidden=48, n_q_heads=6, n_kv_heads=2, ffn=40,
                                             vocab=64, max_pos=16, glu=True, norm_bias=True,
                                             linear_bias=True),
+    "gqa_replicated_kv": oracle.ModelSpec(n_layers=2, hidden=64, n_q_heads=8, n_kv_heads=2, ffn=64, vocab=64,
+                                          glu=True, linear_bias=True),
     "mqa_tied": oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=4, n_kv_heads=1, ffn=64, vocab=32,
                                  tied_embed=True),
 }
 LAYOUTS = [(1, 1, 1, 128), (2, 1, 2, 128), (1, 2, 2, 128), (2, 2, 3, 4), (4, 2, 1, 1), (2, 1, 3, 1),
-           (2, 2, 2, 4, 2), (1, 1, 1, 1, 2), (1, 2, 3, 1, 1)]       # 5th entry: vpp (interleaved stages)
+           (2, 2, 2, 4, 2), (1, 1, 1, 1, 2), (1, 2, 3, 1, 1),       # 5th entry: vpp (interleaved stages)
+           (8, 1, 2, 4)]                                            # TP 8 > n_kv: replicated kv heads
 
 
 def _cases():

@@ -17,6 +17,9 @@ ODD3 = oracle.ModelSpec(n_layers=2, hidden=24, n_q_heads=6, n_kv_heads=3, ffn=42
                         glu=False, tied_embed=False)
 ODD6 = oracle.ModelSpec(n_layers=6, hidden=24, n_q_heads=6, n_kv_heads=6, ffn=42, vocab=48, glu=True)
 
+REP = oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=8, n_kv_heads=2, ffn=24, vocab=16, glu=True,
+                       linear_bias=True)         # TP 4 / 8 > n_kv = 2: kv heads replicated on 2 / 4 ranks
+
 BRUTE = [
     (ODD, (2, 1, 2, 4), (1, 2, 3, 1)),
     (ODD, (1, 2, 3, 1), (2, 2, 1, 4)),
@@ -28,6 +31,9 @@ BRUTE = [
     (ODD6, (2, 3, 2, 1), (1, 1, 3, 4)),
     (ODD6, (2, 3, 2, 1, 2), (3, 1, 1, 4, 3)),        # interleaved stages: vpp 2 -> vpp 3
     (ODD6, (1, 2, 1, 4), (2, 3, 2, 1, 2)),           # plain split -> interleaved
+    (REP, (2, 1, 2, 1), (8, 2, 1, 4)),               # kv heads split -> replicated 4x
+    (REP, (8, 1, 1, 1), (4, 1, 3, 1)),               # replicated 4x -> replicated 2x (replicas corrupted)
+    (REP, (4, 2, 2, 4), (1, 1, 2, 1)),               # replicated 2x -> one rank
 ]
 
 

@@ -79,6 +79,7 @@ def test_7b_state_bytes():
 
 def test_unsupported_combinations():
     spec = oracle.ModelSpec(n_layers=4, hidden=64, n_q_heads=8, n_kv_heads=2, ffn=96, vocab=64)
-    for lay in (oracle.Layout(4, 1, 1), oracle.Layout(1, 3, 1), oracle.Layout(2, 1, 0)):
+    # TP 16 over 2 kv heads would need each group's 4 q heads split 8 ways
+    for lay in (oracle.Layout(16, 1, 1), oracle.Layout(1, 3, 1), oracle.Layout(2, 1, 0)):
         with pytest.raises(ValueError):
             oracle.stage_view(spec, lay, 0, 0)
