@@ -110,6 +110,11 @@ typedef struct {
     int32_t vpp;                        /* model chunks per pipeline stage (interleaved schedule);
                                            0 or 1 = none.  The layers are cut into pp*vpp groups and
                                            stage p holds groups p, p+pp, p+2*pp, ... in that order */
+    int32_t vocab_multiple;             /* > 0: the vocabulary of embed.word / lm_head is padded, per
+                                           world, to a multiple of vocab_multiple*tp rows; every rank
+                                           holds padded/tp rows; rows >= vocab are written +0 in the
+                                           target and never read from the source.  0 = no padding
+                                           (vocab % tp must be 0) */
 } liver_layout_t;
 
 typedef struct {
@@ -153,7 +158,7 @@ typedef struct {
  * return LIVER_E_NO_DEVICE.
  * Errors: INVALID_ARG (null pointer, bad chunk_bytes, non-positive dimension),
  * UNSUPPORTED (n_layers % (pp*vpp), hidden % n_q_heads, n_q_heads % n_kv_heads,
- * ffn % tp or vocab % tp non-zero, kv heads neither split (n_kv_heads % tp == 0) nor
+ * ffn % tp non-zero, vocab % tp non-zero without vocab_multiple, kv heads neither split (n_kv_heads % tp == 0) nor
  * replicated evenly (tp % n_kv_heads == 0 and q heads per group % (tp/n_kv_heads) == 0); only_* out of
  * range or set on the source layout), NOMEM, HIP. */
 int liver_plan_create(const liver_model_spec_t* spec, const liver_layout_t* src,

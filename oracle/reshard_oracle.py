@@ -48,6 +48,11 @@ Megatron-style mixed-parallel training, stated so a reader can check it by eye):
       that order.  Embeddings stay on stage 0, final norm / head on stage PP-1.
   R10 fp32 -> bf16 is round-to-nearest-even on the upper 16 bits; NaN keeps sign
       and upper payload and gets the quiet bit.
+  R11b with vocab_multiple = m > 0 the vocabulary dimension of embed.word / lm_head
+      is padded per world to V_p = ceil(V / (m*TP)) * m*TP rows (what Megatron's
+      make-vocab-size-divisible-by does), so V_p changes with TP.  Every rank
+      holds V_p/TP rows; rows with global index >= V are padding: written +0 in
+      the target, never read from the source.  Logical tensors keep V rows.
   R12 buffer-table index of a rank is tp + TP*(dp + DP*pp).
 
 All data are handled as raw bit patterns (uint16 for bf16, uint32 for fp32):
@@ -92,6 +97,7 @@ class Layout:
     dp: int
     pad_multiple: int = 128
     vpp: int = 1              # R9b: model chunks per stage (interleaved pipeline schedule)
+    vocab_multiple: int = 0   # R11b: pad the vocabulary to a multiple of vocab_multiple*TP rows; 0 = no padding
 
     @property
     def n_ranks(self) -> int:
@@ -109,10 +115,18 @@ def _kv_split_ok(spec: ModelSpec, tp: int) -> bool:
     return tp % spec.n_kv_heads == 0 and (spec.n_q_heads // spec.n_kv_heads) % r == 0
 
 
+def padded_vocab(spec: ModelSpec, lay: Layout) -> int:       # R11b
+    if not lay.vocab_multiple:
+        return spec.vocab
+    q = lay.vocab_multiple * lay.tp
+    return -(-spec.vocab // q) * q
+
+
 def check_supported(spec: ModelSpec, lay: Layout) -> None:
     ok = (lay.vpp >= 1 and spec.n_layers % (lay.pp * lay.vpp) == 0 and spec.hidden % spec.n_q_heads == 0
           and spec.n_q_heads % spec.n_kv_heads == 0 and _kv_split_ok(spec, lay.tp)
-          and spec.ffn % lay.tp == 0 and spec.vocab % lay.tp == 0
+          and spec.ffn % lay.tp == 0 and (spec.vocab % lay.tp == 0 or lay.vocab_multiple > 0)
+          and lay.vocab_multiple >= 0
           and min(lay.tp, lay.pp, lay.dp, lay.pad_multiple) >= 1)
     if not ok:
         raise ValueError(f"unsupported combination {spec} {lay}")
@@ -226,6 +240,12 @@ def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int) -> StageView:
         out.append(PhysParam(phys, (n,) + shapes[name][1:],
                              [Block(name, _rows(tp * n, (tp + 1) * n), _ALL)], canonical))
 
+    def vocab_split(phys: str, name: str, canonical: bool = True) -> None:   # R2 + R11b
+        n = padded_vocab(spec, lay) // TP            # rows per rank, padding included
+        lo, hi = tp * n, min((tp + 1) * n, spec.vocab)
+        blocks = [Block(name, _rows(lo, hi), _rows(0, hi - lo))] if hi > lo else []
+        out.append(PhysParam(phys, (n,) + shapes[name][1:], blocks, canonical))
+
     def split1(phys: str, name: str) -> None:        # R2 row-parallel
         r, c = shapes[name]
         n = c // TP
@@ -263,7 +283,7 @@ def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int) -> StageView:
                              True))
 
     if pp == 0:
-        split0("embed.word", "embed.word")
+        vocab_split("embed.word", "embed.word")
         if spec.max_pos:
             replicated("embed.pos")
     for l in stage_layers(spec, lay, pp):
@@ -291,9 +311,9 @@ def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int) -> StageView:
         if spec.norm_bias:
             replicated("final_norm.b")
         if not spec.tied_embed:
-            split0("lm_head.w", "lm_head.w")
+            vocab_split("lm_head.w", "lm_head.w")
         elif lay.pp > 1:                             # R8: second copy, never the one read
-            split0("embed.word(tied copy)", "embed.word", canonical=False)
+            vocab_split("embed.word(tied copy)", "embed.word", canonical=False)
 
     off = 0
     for prm in out:                                  # R5: back to back, no per-param padding
@@ -367,9 +387,9 @@ def gather_logical(spec: ModelSpec, lay: Layout, kind: int, read: Reader,
 
 
 # ------------------------------------------------------------------------ split
-def build_shard(prm: PhysParam, logical: Dict[str, np.ndarray]) -> np.ndarray:
-    """Local shard of one physical parameter, cut out of the logical tensors."""
-    dtype = logical[prm.blocks[0].name].dtype
+def build_shard(prm: PhysParam, logical: Dict[str, np.ndarray], dtype) -> np.ndarray:
+    """Local shard of one physical parameter, cut out of the logical tensors
+    (elements no block covers -- vocabulary padding -- stay +0)."""
     local = np.zeros(prm.shape, dtype)
     for b in prm.blocks:
         local[b.loc] = logical[b.name][b.idx]
@@ -385,7 +405,7 @@ def split_logical(spec: ModelSpec, lay: Layout, kind: int,
             sv = stage_view(spec, lay, tp, pp)
             flat = np.zeros(sv.n_pad, WORD[kind])
             for prm in sv.params:
-                flat[prm.offset:prm.offset + prm.size] = build_shard(prm, logical).ravel()
+                flat[prm.offset:prm.offset + prm.size] = build_shard(prm, logical, WORD[kind]).ravel()
             for dp in range(lay.dp):
                 if kind == PARAM:
                     out[(lay.rank(tp, pp, dp), kind)] = flat.copy()
@@ -436,11 +456,11 @@ def expected_shards(spec: ModelSpec, lay: Layout, logical: Dict[str, np.ndarray]
         for tp in (range(lay.tp) if tps is None else tps):
             sv = stage_view(spec, lay, tp, pp)
             for prm in sv.params:
-                if all(b.name in have for b in prm.blocks):
-                    yield tp, pp, sv, prm, build_shard(prm, logical)
+                if prm.blocks and all(b.name in have for b in prm.blocks):
+                    yield tp, pp, sv, prm, build_shard(prm, logical, logical[prm.blocks[0].name].dtype)
 
 
 __all__ = ["PARAM", "MASTER", "ADAM_M", "ADAM_V", "KINDS", "WORD", "ModelSpec", "Layout",
-           "check_supported", "logical_tensors", "Block", "PhysParam", "StageView", "stage_layers", "stage_view",
+           "check_supported", "padded_vocab", "logical_tensors", "Block", "PhysParam", "StageView", "stage_layers", "stage_view",
            "buffer_elems", "Reader", "dict_reader", "read_flat", "gather_logical", "build_shard",
            "split_logical", "rne_bf16", "reshard_state", "expected_shards"]

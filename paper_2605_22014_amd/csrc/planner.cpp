@@ -41,15 +41,21 @@ struct Rect {
     bool canonical;  // may a gather read this copy?
 };
 
+struct ZeroRegion {  // flat elements [off, off + n) of a rank column that hold padding, not state
+    int slot;
+    i64 off, n;
+};
+
 struct Column {
     int tp = 0, pp = 0;
     std::vector<Rect> rects;
+    std::vector<ZeroRegion> zeros;  // vocabulary padding rows inside the buffer (the tail pad is added later)
     i64 n_local = 0;
     int last_slot = 0;
 };
 
 // Physical parameter order and shapes of rank column (tp, pp).
-Column build_column(const Geo& g, int TP, int PP, int VPP, int tp, int pp) {
+Column build_column(const Geo& g, int TP, int PP, int VPP, i64 vocab_multiple, int tp, int pp) {
     Column col;
     col.tp = tp;
     col.pp = pp;
@@ -60,9 +66,19 @@ Column build_column(const Geo& g, int TP, int PP, int VPP, int tp, int pp) {
         col.last_slot = slot;
     };
     const bool lead = (tp == 0);  // TP-replicated parameters are read from tp 0
-    const i64 g_loc = g.nkv / TP, fn = g.F / TP, qn = g.Q / TP, vn = g.V / TP;
+    const i64 g_loc = g.nkv / TP, fn = g.F / TP, qn = g.Q / TP;
+    // rows of embed.word / lm_head per rank; with vocab_multiple the vocabulary is padded to a multiple of
+    // vocab_multiple*TP rows: rows >= V hold no state (zero in the target, never read from the source)
+    const i64 vn = vocab_multiple > 0 ? (g.V + vocab_multiple * TP - 1) / (vocab_multiple * TP) * vocab_multiple : g.V / TP;
+    auto add_vocab = [&](int tensor, int slot, bool canonical) {
+        const i64 lo = tp * vn, hi = std::min(lo + vn, g.V), real = hi > lo ? (hi - lo) * g.H : 0;
+        if (real > 0) col.rects.push_back({tensor, slot, lo, hi, 0, g.H, off, canonical});
+        if (real < vn * g.H) col.zeros.push_back({slot, off + real, vn * g.H - real});
+        off += vn * g.H;
+        col.last_slot = slot;
+    };
     if (pp == 0) {
-        add(T_EMBED_WORD, 0, tp * vn, (tp + 1) * vn, 0, g.H, true);
+        add_vocab(T_EMBED_WORD, 0, true);
         if (g.P) add(T_EMBED_POS, 0, 0, g.P, 0, g.H, lead);
     }
     const i64 per = g.L / ((i64)PP * VPP);  // layers per model chunk; stage pp holds chunks pp, pp+PP, ...
@@ -117,9 +133,9 @@ Column build_column(const Geo& g, int TP, int PP, int VPP, int tp, int pp) {
         add(T_FINAL_W, slot, 0, 1, 0, g.H, lead);
         if (g.norm_bias) add(T_FINAL_B, slot, 0, 1, 0, g.H, lead);
         if (!g.tied)
-            add(T_LM_HEAD, slot, tp * vn, (tp + 1) * vn, 0, g.H, true);
+            add_vocab(T_LM_HEAD, slot, true);
         else if (PP > 1)  // second copy of the tied embedding: written, never read
-            add(T_EMBED_WORD, slot, tp * vn, (tp + 1) * vn, 0, g.H, false);
+            add_vocab(T_EMBED_WORD, slot, false);
     }
     col.n_local = off;
     return col;
@@ -275,26 +291,28 @@ struct Builder {
     void zero_padding(const Column& col) {
         const liver_layout_t& D = plan.dst;
         const StageSize& st = plan.dst_stage[col.pp];
-        if (st.n_pad == st.n_local) return;
-        for (int dp = 0; dp < D.dp; ++dp) {
-            if (!dst_dp_planned(dp)) continue;
-            const int rank = rank_of(D, col.tp, col.pp, dp);
-            for (int k = 0; k < LIVER_NUM_KINDS; ++k) {
-                if (!kind_on(k)) continue;
-                i64 lo = st.n_local, hi = st.n_pad, base = 0;
-                if (k != LIVER_PARAM_BF16) {
-                    base = dp * st.S;
-                    lo = std::max(lo, base);
-                    hi = std::min(hi, base + st.S);
+        std::vector<ZeroRegion> regions = col.zeros;  // vocabulary padding rows ...
+        if (st.n_pad > st.n_local) regions.push_back({col.last_slot, st.n_local, st.n_pad - st.n_local});  // ... and the tail
+        for (const ZeroRegion& z : regions)
+            for (int dp = 0; dp < D.dp; ++dp) {
+                if (!dst_dp_planned(dp)) continue;
+                const int rank = rank_of(D, col.tp, col.pp, dp);
+                for (int k = 0; k < LIVER_NUM_KINDS; ++k) {
+                    if (!kind_on(k)) continue;
+                    i64 lo = z.off, hi = z.off + z.n, base = 0;
+                    if (k != LIVER_PARAM_BF16) {  // this DP rank's slice of the fp32 buffers
+                        base = dp * st.S;
+                        lo = std::max(lo, base);
+                        hi = std::min(hi, base + st.S);
+                    }
+                    if (lo >= hi) continue;
+                    Entry e;
+                    e.slot = z.slot;
+                    e.run = hi - lo;
+                    e.dsts.push_back({rank, k, LIVER_OP_ZERO, lo - base, hi - lo});
+                    push_bounded(std::move(e));
                 }
-                if (lo >= hi) continue;
-                Entry e;
-                e.slot = col.last_slot;
-                e.run = hi - lo;
-                e.dsts.push_back({rank, k, LIVER_OP_ZERO, lo - base, hi - lo});
-                push_bounded(std::move(e));
             }
-        }
     }
 
     int run();
@@ -311,8 +329,8 @@ int Builder::run() {
         return LIVER_E_INVALID_ARG;
     }
     for (const liver_layout_t* l : {&S, &D})
-        if (l->tp <= 0 || l->pp <= 0 || l->dp <= 0 || l->pad_multiple <= 0 || l->vpp < 0) {
-            why = "layout: tp, pp, dp, pad_multiple must be positive, vpp non-negative";
+        if (l->tp <= 0 || l->pp <= 0 || l->dp <= 0 || l->pad_multiple <= 0 || l->vpp < 0 || l->vocab_multiple < 0) {
+            why = "layout: tp, pp, dp, pad_multiple must be positive, vpp and vocab_multiple non-negative";
             return LIVER_E_INVALID_ARG;
         }
     if (plan.chunk_bytes < 256 || plan.chunk_bytes % 256) {
@@ -326,7 +344,7 @@ int Builder::run() {
     for (const liver_layout_t* l : {&S, &D}) {
         const bool kv_ok = sp.n_kv_heads % l->tp == 0 ||
                            (l->tp % sp.n_kv_heads == 0 && (sp.n_q_heads / sp.n_kv_heads) % (l->tp / sp.n_kv_heads) == 0);
-        if (sp.n_layers % (l->pp * vpp_of(*l)) || !kv_ok || sp.ffn % l->tp || sp.vocab % l->tp) {
+        if (sp.n_layers % (l->pp * vpp_of(*l)) || !kv_ok || sp.ffn % l->tp || (sp.vocab % l->tp && l->vocab_multiple == 0)) {
             why = "n_layers % (pp*vpp), ffn % tp or vocab % tp != 0, or kv heads neither split nor replicated evenly over tp";
             return LIVER_E_UNSUPPORTED;
         }
@@ -356,7 +374,7 @@ int Builder::run() {
         const i64 quantum = (i64)lay.dp * lay.pad_multiple;
         for (int pp = 0; pp < lay.pp; ++pp) {
             StageSize s;
-            s.n_local = build_column(g, lay.tp, lay.pp, vpp_of(lay), 0, pp).n_local;
+            s.n_local = build_column(g, lay.tp, lay.pp, vpp_of(lay), lay.vocab_multiple, 0, pp).n_local;
             s.n_pad = (s.n_local + quantum - 1) / quantum * quantum;
             s.S = s.n_pad / lay.dp;
             out[pp] = s;
@@ -373,7 +391,7 @@ int Builder::run() {
     std::vector<std::vector<SrcRect>> by_tensor(n_tensors);  // pruning: only views of the same tensor meet
     for (int pp = 0; pp < S.pp; ++pp)
         for (int tp = 0; tp < S.tp; ++tp) {
-            Column c = build_column(g, S.tp, S.pp, vpp_of(S), tp, pp);
+            Column c = build_column(g, S.tp, S.pp, vpp_of(S), S.vocab_multiple, tp, pp);
             for (const Rect& r : c.rects)
                 if (r.canonical) by_tensor[r.tensor].push_back({r, tp, pp});
         }
@@ -387,7 +405,7 @@ int Builder::run() {
         if (D.only_pp >= 0 && D.only_pp != pp) continue;
         for (int tp = 0; tp < D.tp; ++tp) {
             if (D.only_tp >= 0 && D.only_tp != tp) continue;
-            Column col = build_column(g, D.tp, D.pp, vpp_of(D), tp, pp);
+            Column col = build_column(g, D.tp, D.pp, vpp_of(D), D.vocab_multiple, tp, pp);
             std::vector<Piece> pieces;
             for (const Rect& d : col.rects) {
                 const i64 dw = d.c1 - d.c0;

@@ -45,11 +45,17 @@ def layer_param_sizes(spec, TP, l):
     return out
 
 
-def stage_param_sizes(spec, TP, PP, pp, vpp=1):
+def vocab_rows(spec, TP, vm=0):
+    """Rows of embed.word / lm_head per TP rank; vm > 0 pads the vocabulary to a multiple of vm*TP."""
+    V = spec.vocab
+    return V // TP if not vm else (V + vm * TP - 1) // (vm * TP) * vm
+
+
+def stage_param_sizes(spec, TP, PP, pp, vpp=1, vm=0):
     H, hd, Q, KV, F, V = dims(spec)
     out = []
     if pp == 0:
-        out.append(("embed.word", V * H // TP))
+        out.append(("embed.word", vocab_rows(spec, TP, vm) * H))
         if spec.max_pos:
             out.append(("embed.pos", spec.max_pos * H))
     c = spec.n_layers // (PP * vpp)         # layers per model chunk; stage pp holds chunks pp, pp+PP, ...
@@ -62,22 +68,22 @@ def stage_param_sizes(spec, TP, PP, pp, vpp=1):
         if spec.norm_bias:
             out.append(("final_norm.b", H))
         if not spec.tied_embed:
-            out.append(("lm_head.w", V * H // TP))
+            out.append(("lm_head.w", vocab_rows(spec, TP, vm) * H))
         elif PP > 1:
-            out.append(("embed.word(tied copy)", V * H // TP))
+            out.append(("embed.word(tied copy)", vocab_rows(spec, TP, vm) * H))
     return out
 
 
-def n_local(spec, TP, PP, pp, vpp=1):
-    return sum(n for _, n in stage_param_sizes(spec, TP, PP, pp, vpp))
+def n_local(spec, TP, PP, pp, vpp=1, vm=0):
+    return sum(n for _, n in stage_param_sizes(spec, TP, PP, pp, vpp, vm))
 
 
-def n_pad(spec, TP, PP, DP, pad_multiple, pp, vpp=1):
+def n_pad(spec, TP, PP, DP, pad_multiple, pp, vpp=1, vm=0):
     q = DP * pad_multiple
-    return (n_local(spec, TP, PP, pp, vpp) + q - 1) // q * q
+    return (n_local(spec, TP, PP, pp, vpp, vm) + q - 1) // q * q
 
 
-def owner(spec, TP, tp, phys, k):
+def owner(spec, TP, tp, phys, k, vm=0):
     """(names, idx): logical tensor name and row-major logical index of local
     elements k (int64 array) of physical parameter `phys` on TP rank `tp`."""
     H, hd, Q, KV, F, V = dims(spec)
@@ -91,9 +97,11 @@ def owner(spec, TP, tp, phys, k):
                 "final_norm.b", "embed.pos"):                    # replicated
         names[:] = base
         return names, k
-    if leaf in ("embed.word", "lm_head.w"):                      # column-parallel [V, H]
+    if leaf in ("embed.word", "lm_head.w"):                      # column-parallel [V, H], maybe padded
+        idx = tp * vocab_rows(spec, TP, vm) * H + k
         names[:] = base
-        return names, tp * (V // TP) * H + k
+        names[idx >= V * H] = None                               # vocabulary padding: owns nothing
+        return names, np.where(idx >= V * H, 0, idx)
     if leaf == "o.w":                                            # row-parallel [H, Q]
         w = Q // TP
         names[:] = base
@@ -143,14 +151,15 @@ def owner(spec, TP, tp, phys, k):
     raise KeyError(phys)
 
 
-def column_ownership(spec, TP, PP, tp, pp, vpp=1):
+def column_ownership(spec, TP, PP, tp, pp, vpp=1, vm=0):
     """For flat offsets 0..N_local-1 of rank column (tp, pp): (names, idx, canonical).
+    names[k] is None where the element is vocabulary padding.
 
     canonical[k] is False where the element is a replica that a gather must not
     read: TP-replicated parameters on tp > 0 and the tied-embedding copy."""
     names, idx, canon = [], [], []
-    for phys, n in stage_param_sizes(spec, TP, PP, pp, vpp):
-        nm, ix = owner(spec, TP, tp, phys, np.arange(n, dtype=np.int64))
+    for phys, n in stage_param_sizes(spec, TP, PP, pp, vpp, vm):
+        nm, ix = owner(spec, TP, tp, phys, np.arange(n, dtype=np.int64), vm)
         names.append(nm)
         idx.append(ix)
         leaf = phys.split(".", 1)[1] if phys.startswith("L") else phys

@@ -21,12 +21,16 @@ SPECS = {
                                             linear_bias=True),
     "gqa_replicated_kv": oracle.ModelSpec(n_layers=2, hidden=64, n_q_heads=8, n_kv_heads=2, ffn=64, vocab=64,
                                           glu=True, linear_bias=True),
+    "odd_vocab_tied": oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=4, n_kv_heads=4, ffn=32, vocab=50,
+                                       max_pos=8, tied_embed=True),
+    "odd_vocab_head": oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=4, n_kv_heads=4, ffn=32, vocab=37, glu=True),
     "mqa_tied": oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=4, n_kv_heads=1, ffn=64, vocab=32,
                                  tied_embed=True),
 }
 LAYOUTS = [(1, 1, 1, 128), (2, 1, 2, 128), (1, 2, 2, 128), (2, 2, 3, 4), (4, 2, 1, 1), (2, 1, 3, 1),
            (2, 2, 2, 4, 2), (1, 1, 1, 1, 2), (1, 2, 3, 1, 1),       # 5th entry: vpp (interleaved stages)
-           (8, 1, 2, 4)]                                            # TP 8 > n_kv: replicated kv heads
+           (8, 1, 2, 4),                                            # TP 8 > n_kv: replicated kv heads
+           (2, 2, 2, 4, 1, 8), (4, 1, 1, 1, 1, 4), (1, 1, 2, 1, 1, 16), (4, 2, 3, 128, 1, 32)]   # 6th: vocab_multiple
 
 
 def _cases():
@@ -37,7 +41,7 @@ def _cases():
                 oracle.check_supported(spec, lay)
             except ValueError:
                 continue
-            yield pytest.param(spec, lay, id=f"{sname}-tp{tp}pp{pp}dp{dp}pm{pm}v{lay.vpp}")
+            yield pytest.param(spec, lay, id=f"{sname}-tp{tp}pp{pp}dp{dp}pm{pm}v{lay.vpp}vm{lay.vocab_multiple}")
 
 
 def _tensor_ordinal_state(spec):
@@ -57,15 +61,15 @@ def test_split_matches_ownership(spec, lay):
     w_hi = make_world(spec, lay, synth.index_encoded_state(shapes, half=1), poison=False)
     w_ord = make_world(spec, lay, _tensor_ordinal_state(spec), poison=False)
     for pp in range(lay.pp):
-        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp)
+        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp, lay.vocab_multiple)
         S = npad // lay.dp
         for tp in range(lay.tp):
-            names, idx, _ = own.column_ownership(spec, lay.tp, lay.pp, tp, pp, lay.vpp)
+            names, idx, _ = own.column_ownership(spec, lay.tp, lay.pp, tp, pp, lay.vpp, lay.vocab_multiple)
             nl = len(names)
             exp_idx = np.zeros(npad, np.int64)
             exp_idx[:nl] = idx
             exp_ord = np.zeros(npad, np.int64)
-            exp_ord[:nl] = [ordinal[n] for n in names]
+            exp_ord[:nl] = [ordinal.get(n, 0) for n in names]       # vocabulary padding owns nothing: 0
             for dp in range(lay.dp):
                 r = lay.rank(tp, pp, dp)
                 assert np.array_equal(w_idx[(r, oracle.PARAM)], (exp_idx & 0xFFFF).astype(np.uint16))
@@ -135,3 +139,19 @@ def test_interleaved_stage_layers():
     assert order == ["L2", "L3", "L6", "L7"]
     with pytest.raises(ValueError):
         oracle.stage_view(spec, oracle.Layout(1, 4, 1, 1, 4), 0, 0)
+
+
+def test_padded_vocab_sizes():
+    """GPT-2's 50257-token vocabulary padded to a multiple of 128*TP rows: 50304 / 50432 / 50688 for TP 1 / 2 / 4
+    (the sizes Megatron-LM reports for make-vocab-size-divisible-by 128)."""
+    spec = oracle.ModelSpec(n_layers=2, hidden=64, n_q_heads=4, n_kv_heads=4, ffn=64, vocab=50257, tied_embed=True)
+    for tp, want in ((1, 50304), (2, 50432), (4, 50688)):
+        lay = oracle.Layout(tp, 1, 1, 128, 1, 128)
+        assert oracle.padded_vocab(spec, lay) == want == own.vocab_rows(spec, tp, 128) * tp
+        sv = oracle.stage_view(spec, lay, tp - 1, 0)
+        emb = sv.params[0]
+        assert emb.shape == (want // tp, 64)
+        real = max(0, min(want // tp, 50257 - (tp - 1) * (want // tp)))
+        assert sum(b.loc[0].stop - b.loc[0].start for b in emb.blocks) == real
+    with pytest.raises(ValueError):
+        oracle.stage_view(spec, oracle.Layout(2, 1, 1, 128), 0, 0)        # 50257 % 2 != 0 and no padding

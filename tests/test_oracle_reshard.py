@@ -20,6 +20,10 @@ ODD6 = oracle.ModelSpec(n_layers=6, hidden=24, n_q_heads=6, n_kv_heads=6, ffn=42
 REP = oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=8, n_kv_heads=2, ffn=24, vocab=16, glu=True,
                        linear_bias=True)         # TP 4 / 8 > n_kv = 2: kv heads replicated on 2 / 4 ranks
 
+VOC = oracle.ModelSpec(n_layers=2, hidden=16, n_q_heads=4, n_kv_heads=4, ffn=16, vocab=50, max_pos=3,
+                       tied_embed=True)          # 50 rows never divide evenly: padded per world
+VOCH = oracle.ModelSpec(n_layers=2, hidden=16, n_q_heads=4, n_kv_heads=2, ffn=16, vocab=37, glu=True)
+
 BRUTE = [
     (ODD, (2, 1, 2, 4), (1, 2, 3, 1)),
     (ODD, (1, 2, 3, 1), (2, 2, 1, 4)),
@@ -34,6 +38,10 @@ BRUTE = [
     (REP, (2, 1, 2, 1), (8, 2, 1, 4)),               # kv heads split -> replicated 4x
     (REP, (8, 1, 1, 1), (4, 1, 3, 1)),               # replicated 4x -> replicated 2x (replicas corrupted)
     (REP, (4, 2, 2, 4), (1, 1, 2, 1)),               # replicated 2x -> one rank
+    (VOC, (2, 1, 2, 4, 1, 8), (4, 2, 1, 1, 1, 4)),   # padded vocabulary 64 -> 64 rows, other split (6th = vocab_multiple)
+    (VOC, (1, 2, 1, 1, 1, 0), (4, 1, 3, 4, 1, 16)),  # unpadded 50 -> padded 64, tied copy dropped (corrupted pads)
+    (VOCH, (2, 1, 3, 1, 1, 5), (1, 2, 2, 128, 1, 3)),   # 40 -> 39 rows, untied head
+    (VOCH, (1, 1, 1, 1, 1, 64), (4, 2, 1, 1, 1, 16)),   # tp 3 holds rows 48..63: all padding (and kv heads replicated)
 ]
 
 

@@ -20,8 +20,8 @@ def poison_pads(spec, lay, bufs):
     """Overwrite the padding of every buffer of world `lay` with NaN sentinels
     (source padding must never be read by a reshard)."""
     for pp in range(lay.pp):
-        nl = own.n_local(spec, lay.tp, lay.pp, pp, lay.vpp)
-        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp)
+        nl = own.n_local(spec, lay.tp, lay.pp, pp, lay.vpp, lay.vocab_multiple)
+        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp, lay.vocab_multiple)
         S = npad // lay.dp
         for tp in range(lay.tp):
             for dp in range(lay.dp):
@@ -46,13 +46,13 @@ def make_world(spec, lay, state, poison=True, kinds=oracle.KINDS):
 def corrupt_replicas(spec, lay, bufs):
     """Flip bits in every copy a gather must NOT read, located by the ownership
     formulas (not by the oracle): TP-replicated parameters on tp > 0, the tied
-    embedding copy, and PARAM replicas with dp > 0."""
+    embedding copy, PARAM replicas with dp > 0, and vocabulary padding rows."""
     for pp in range(lay.pp):
-        nl = own.n_local(spec, lay.tp, lay.pp, pp, lay.vpp)
-        S = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp) // lay.dp
+        nl = own.n_local(spec, lay.tp, lay.pp, pp, lay.vpp, lay.vocab_multiple)
+        S = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp, lay.vocab_multiple) // lay.dp
         for tp in range(lay.tp):
-            _, _, canon = own.column_ownership(spec, lay.tp, lay.pp, tp, pp, lay.vpp)
-            bad = np.flatnonzero(~canon)
+            names, _, canon = own.column_ownership(spec, lay.tp, lay.pp, tp, pp, lay.vpp, lay.vocab_multiple)
+            bad = np.flatnonzero(~canon | np.equal(names, None))       # copies, and vocabulary padding
             for dp in range(lay.dp):
                 r = lay.rank(tp, pp, dp)
                 if dp > 0:
@@ -81,12 +81,12 @@ def brute_reshard(spec, src, dst, src_bufs, derive=False):
     alone (tiny models only).  Independent of the oracle's slicing."""
     value = {k: {} for k in oracle.KINDS}
     for pp in range(src.pp):
-        npad = own.n_pad(spec, src.tp, src.pp, src.dp, src.pad_multiple, pp, src.vpp)
+        npad = own.n_pad(spec, src.tp, src.pp, src.dp, src.pad_multiple, pp, src.vpp, src.vocab_multiple)
         S = npad // src.dp
         for tp in range(src.tp):
-            names, idx, canon = own.column_ownership(spec, src.tp, src.pp, tp, pp, src.vpp)
+            names, idx, canon = own.column_ownership(spec, src.tp, src.pp, tp, pp, src.vpp, src.vocab_multiple)
             for k in range(len(names)):
-                if not canon[k]:
+                if not canon[k] or names[k] is None:
                     continue
                 key = (names[k], int(idx[k]))
                 assert key not in value[oracle.PARAM], ("owned twice", key)
@@ -98,12 +98,14 @@ def brute_reshard(spec, src, dst, src_bufs, derive=False):
         value[oracle.PARAM] = {key: _rne_scalar(int(v)) for key, v in value[oracle.MASTER].items()}
     out = {}
     for pp in range(dst.pp):
-        npad = own.n_pad(spec, dst.tp, dst.pp, dst.dp, dst.pad_multiple, pp, dst.vpp)
+        npad = own.n_pad(spec, dst.tp, dst.pp, dst.dp, dst.pad_multiple, pp, dst.vpp, dst.vocab_multiple)
         S = npad // dst.dp
         for tp in range(dst.tp):
-            names, idx, _ = own.column_ownership(spec, dst.tp, dst.pp, tp, pp, dst.vpp)
+            names, idx, _ = own.column_ownership(spec, dst.tp, dst.pp, tp, pp, dst.vpp, dst.vocab_multiple)
             flat = {kind: np.zeros(npad, oracle.WORD[kind]) for kind in oracle.KINDS}
             for k in range(len(names)):
+                if names[k] is None:            # vocabulary padding stays +0
+                    continue
                 key = (names[k], int(idx[k]))
                 for kind in oracle.KINDS:
                     flat[kind][k] = value[kind][key]
