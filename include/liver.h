@@ -115,6 +115,9 @@ typedef struct {
                                            holds padded/tp rows; rows >= vocab are written +0 in the
                                            target and never read from the source.  0 = no padding
                                            (vocab % tp must be 0) */
+    int32_t pp_first, pp_last;          /* > 0: number of layers on the first / last pipeline stage; the
+                                           other stages share the remaining layers evenly.  0 = even
+                                           split.  Not combinable with vpp > 1 */
 } liver_layout_t;
 
 typedef struct {
@@ -157,7 +160,7 @@ typedef struct {
  * not, the plan is host-only: it can be inspected but pack / unpack / reshard
  * return LIVER_E_NO_DEVICE.
  * Errors: INVALID_ARG (null pointer, bad chunk_bytes, non-positive dimension),
- * UNSUPPORTED (n_layers % (pp*vpp), hidden % n_q_heads, n_q_heads % n_kv_heads,
+ * UNSUPPORTED (layers do not split over the stages as asked, hidden % n_q_heads, n_q_heads % n_kv_heads,
  * ffn % tp non-zero, vocab % tp non-zero without vocab_multiple, kv heads neither split (n_kv_heads % tp == 0) nor
  * replicated evenly (tp % n_kv_heads == 0 and q heads per group % (tp/n_kv_heads) == 0); only_* out of
  * range or set on the source layout), NOMEM, HIP. */

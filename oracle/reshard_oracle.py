@@ -46,6 +46,9 @@ Megatron-style mixed-parallel training, stated so a reader can check it by eye):
       Section 4.7 mentions) the layers are cut into PP*vpp groups of c layers and
       stage pp owns groups pp, pp+PP, pp+2*PP, ...; they sit in its flat buffer in
       that order.  Embeddings stay on stage 0, final norm / head on stage PP-1.
+  R9c uneven split: pp_first / pp_last give the layer count of the first / last
+      stage (the stages that also hold the embedding / the head); the other stages
+      share the remaining layers evenly.
   R10 fp32 -> bf16 is round-to-nearest-even on the upper 16 bits; NaN keeps sign
       and upper payload and gets the quiet bit.
   R11b with vocab_multiple = m > 0 the vocabulary dimension of embed.word / lm_head
@@ -98,6 +101,8 @@ class Layout:
     pad_multiple: int = 128
     vpp: int = 1              # R9b: model chunks per stage (interleaved pipeline schedule)
     vocab_multiple: int = 0   # R11b: pad the vocabulary to a multiple of vocab_multiple*TP rows; 0 = no padding
+    pp_first: int = 0         # R9c: layers on the first / last stage (0 = even share); the other
+    pp_last: int = 0          #      stages split the remaining layers evenly
 
     @property
     def n_ranks(self) -> int:
@@ -123,7 +128,7 @@ def padded_vocab(spec: ModelSpec, lay: Layout) -> int:       # R11b
 
 
 def check_supported(spec: ModelSpec, lay: Layout) -> None:
-    ok = (lay.vpp >= 1 and spec.n_layers % (lay.pp * lay.vpp) == 0 and spec.hidden % spec.n_q_heads == 0
+    ok = (lay.vpp >= 1 and _stage_counts(spec, lay) is not None and spec.hidden % spec.n_q_heads == 0
           and spec.n_q_heads % spec.n_kv_heads == 0 and _kv_split_ok(spec, lay.tp)
           and spec.ffn % lay.tp == 0 and (spec.vocab % lay.tp == 0 or lay.vocab_multiple > 0)
           and lay.vocab_multiple >= 0
@@ -216,8 +221,30 @@ def _cols(a: int, b: int) -> Tuple[slice, ...]:
 _ALL: Tuple[slice, ...] = (slice(None),)
 
 
+def _stage_counts(spec: ModelSpec, lay: Layout) -> Optional[List[int]]:
+    """Layers per stage, or None if the split is not possible (R9, R9c)."""
+    L, PP = spec.n_layers, lay.pp
+    if lay.pp_first < 0 or lay.pp_last < 0 or min(lay.tp, lay.pp, lay.dp) < 1:
+        return None
+    if not lay.pp_first and not lay.pp_last:
+        return [L // PP] * PP if L % (PP * lay.vpp) == 0 else None
+    fixed = (1 if lay.pp_first else 0) + (1 if lay.pp_last else 0)
+    rest, others = L - lay.pp_first - lay.pp_last, PP - fixed
+    if lay.vpp != 1 or others < 0 or rest < 0 or (others == 0 and rest != 0) or (others > 0 and rest % others):
+        return None
+    counts = [rest // others if others else 0] * PP
+    if lay.pp_first:
+        counts[0] = lay.pp_first
+    if lay.pp_last:
+        counts[-1] = lay.pp_last
+    return counts if min(counts) >= 1 else None
+
+
 def stage_layers(spec: ModelSpec, lay: Layout, pp: int) -> List[int]:
     """Layers held by stage pp, in the order they sit in its flat buffer (R9)."""
+    if lay.pp_first or lay.pp_last:                  # R9c: uneven first / last stage
+        counts = _stage_counts(spec, lay)
+        return list(range(sum(counts[:pp]), sum(counts[:pp + 1])))
     c = spec.n_layers // (lay.pp * lay.vpp)          # layers per model chunk
     return [l for v in range(lay.vpp) for l in range((v * lay.pp + pp) * c, (v * lay.pp + pp + 1) * c)]
 

@@ -44,7 +44,7 @@ class _Spec(C.Structure):
 
 class _Layout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("tp", "pp", "dp", "pad_multiple", "only_tp", "only_pp", "only_dp")] \
-        + [("flags", C.c_uint32), ("kind_mask", C.c_uint32), ("vpp", C.c_int32), ("vocab_multiple", C.c_int32)]
+        + [("flags", C.c_uint32), ("kind_mask", C.c_uint32), ("vpp", C.c_int32), ("vocab_multiple", C.c_int32), ("pp_first", C.c_int32), ("pp_last", C.c_int32)]
 
 
 class PlanInfo(C.Structure):
@@ -93,6 +93,8 @@ class Layout:
     kinds: Optional[Tuple[int, ...]] = None      # None = all four
     vpp: int = 1                                 # model chunks per stage (interleaved pipeline)
     vocab_multiple: int = 0                      # pad the vocabulary to a multiple of vocab_multiple*tp rows
+    pp_first: int = 0                            # layers on the first / last stage (0 = even split)
+    pp_last: int = 0
 
     @property
     def n_ranks(self) -> int:
@@ -104,7 +106,7 @@ class Layout:
     def _c(self) -> _Layout:
         mask = 0 if self.kinds is None else sum(1 << k for k in set(self.kinds))
         return _Layout(self.tp, self.pp, self.dp, self.pad_multiple, self.only_tp, self.only_pp, self.only_dp,
-                       _DERIVE * self.derive_bf16, mask, self.vpp, self.vocab_multiple)
+                       _DERIVE * self.derive_bf16, mask, self.vpp, self.vocab_multiple, self.pp_first, self.pp_last)
 
 
 def _load() -> C.CDLL:

@@ -55,7 +55,35 @@ struct Column {
 };
 
 // Physical parameter order and shapes of rank column (tp, pp).
-Column build_column(const Geo& g, int TP, int PP, int VPP, i64 vocab_multiple, int tp, int pp) {
+// Layers of stage pp in flat-buffer order: an even split, vpp interleaved model chunks, or an uneven split
+// with a fixed layer count on the first / last stage.  Empty if the split is impossible.
+std::vector<i64> stage_layers(i64 L, const liver_layout_t& lay, int pp) {
+    const int PP = lay.pp, VPP = lay.vpp > 1 ? lay.vpp : 1;
+    std::vector<i64> out;
+    if (lay.pp_first > 0 || lay.pp_last > 0) {
+        const int others = PP - (lay.pp_first > 0) - (lay.pp_last > 0);
+        const i64 rest = L - lay.pp_first - lay.pp_last;
+        if (VPP != 1 || others < 0 || rest < 0 || (others == 0 && rest != 0) || (others > 0 && (rest % others || rest == 0)))
+            return out;
+        auto count = [&](int p) -> i64 {
+            if (p == 0 && lay.pp_first > 0) return lay.pp_first;
+            if (p == PP - 1 && lay.pp_last > 0) return lay.pp_last;
+            return rest / others;
+        };
+        i64 lo = 0;
+        for (int p = 0; p < pp; ++p) lo += count(p);
+        for (i64 l = lo; l < lo + count(pp); ++l) out.push_back(l);
+        return out;
+    }
+    if (L % ((i64)PP * VPP)) return out;
+    const i64 per = L / ((i64)PP * VPP);  // layers per model chunk; stage pp holds chunks pp, pp+PP, ...
+    for (i64 li = 0; li < per * VPP; ++li) out.push_back(((li / per) * PP + pp) * per + li % per);
+    return out;
+}
+
+Column build_column(const Geo& g, const liver_layout_t& lay, int tp, int pp) {
+    const int TP = lay.tp, PP = lay.pp;
+    const i64 vocab_multiple = lay.vocab_multiple;
     Column col;
     col.tp = tp;
     col.pp = pp;
@@ -81,9 +109,7 @@ Column build_column(const Geo& g, int TP, int PP, int VPP, i64 vocab_multiple, i
         add_vocab(T_EMBED_WORD, 0, true);
         if (g.P) add(T_EMBED_POS, 0, 0, g.P, 0, g.H, lead);
     }
-    const i64 per = g.L / ((i64)PP * VPP);  // layers per model chunk; stage pp holds chunks pp, pp+PP, ...
-    for (i64 li = 0; li < per * VPP; ++li) {
-        const i64 l = ((li / per) * PP + pp) * per + li % per;
+    for (const i64 l : stage_layers(g.L, lay, pp)) {
         const int slot = 1 + (int)l;
         const int b = T_GLOBALS + (int)l * T_PER_LAYER;
         add(b + LN1_W, slot, 0, 1, 0, g.H, lead);
@@ -154,7 +180,6 @@ struct Entry {
 };
 
 inline int elem_bytes(int kind) { return kind == LIVER_PARAM_BF16 ? 2 : 4; }
-inline int vpp_of(const liver_layout_t& l) { return l.vpp > 1 ? l.vpp : 1; }
 
 // Payload elements [p0, p1) of `e` (row-major over rows x run) as up to three
 // pieces: the tail of a row, whole rows, the head of a row.
@@ -329,8 +354,9 @@ int Builder::run() {
         return LIVER_E_INVALID_ARG;
     }
     for (const liver_layout_t* l : {&S, &D})
-        if (l->tp <= 0 || l->pp <= 0 || l->dp <= 0 || l->pad_multiple <= 0 || l->vpp < 0 || l->vocab_multiple < 0) {
-            why = "layout: tp, pp, dp, pad_multiple must be positive, vpp and vocab_multiple non-negative";
+        if (l->tp <= 0 || l->pp <= 0 || l->dp <= 0 || l->pad_multiple <= 0 || l->vpp < 0 || l->vocab_multiple < 0 ||
+            l->pp_first < 0 || l->pp_last < 0) {
+            why = "layout: tp, pp, dp, pad_multiple must be positive, vpp, vocab_multiple, pp_first, pp_last non-negative";
             return LIVER_E_INVALID_ARG;
         }
     if (plan.chunk_bytes < 256 || plan.chunk_bytes % 256) {
@@ -344,8 +370,10 @@ int Builder::run() {
     for (const liver_layout_t* l : {&S, &D}) {
         const bool kv_ok = sp.n_kv_heads % l->tp == 0 ||
                            (l->tp % sp.n_kv_heads == 0 && (sp.n_q_heads / sp.n_kv_heads) % (l->tp / sp.n_kv_heads) == 0);
-        if (sp.n_layers % (l->pp * vpp_of(*l)) || !kv_ok || sp.ffn % l->tp || (sp.vocab % l->tp && l->vocab_multiple == 0)) {
-            why = "n_layers % (pp*vpp), ffn % tp or vocab % tp != 0, or kv heads neither split nor replicated evenly over tp";
+        bool stages_ok = true;
+        for (int p = 0; p < l->pp; ++p) stages_ok = stages_ok && !stage_layers(sp.n_layers, *l, p).empty();
+        if (!stages_ok || !kv_ok || sp.ffn % l->tp || (sp.vocab % l->tp && l->vocab_multiple == 0)) {
+            why = "layers do not split over the stages, ffn % tp or vocab % tp != 0, or kv heads neither split nor replicated evenly over tp";
             return LIVER_E_UNSUPPORTED;
         }
     }
@@ -374,7 +402,7 @@ int Builder::run() {
         const i64 quantum = (i64)lay.dp * lay.pad_multiple;
         for (int pp = 0; pp < lay.pp; ++pp) {
             StageSize s;
-            s.n_local = build_column(g, lay.tp, lay.pp, vpp_of(lay), lay.vocab_multiple, 0, pp).n_local;
+            s.n_local = build_column(g, lay, 0, pp).n_local;
             s.n_pad = (s.n_local + quantum - 1) / quantum * quantum;
             s.S = s.n_pad / lay.dp;
             out[pp] = s;
@@ -391,7 +419,7 @@ int Builder::run() {
     std::vector<std::vector<SrcRect>> by_tensor(n_tensors);  // pruning: only views of the same tensor meet
     for (int pp = 0; pp < S.pp; ++pp)
         for (int tp = 0; tp < S.tp; ++tp) {
-            Column c = build_column(g, S.tp, S.pp, vpp_of(S), S.vocab_multiple, tp, pp);
+            Column c = build_column(g, S, tp, pp);
             for (const Rect& r : c.rects)
                 if (r.canonical) by_tensor[r.tensor].push_back({r, tp, pp});
         }
@@ -405,7 +433,7 @@ int Builder::run() {
         if (D.only_pp >= 0 && D.only_pp != pp) continue;
         for (int tp = 0; tp < D.tp; ++tp) {
             if (D.only_tp >= 0 && D.only_tp != tp) continue;
-            Column col = build_column(g, D.tp, D.pp, vpp_of(D), D.vocab_multiple, tp, pp);
+            Column col = build_column(g, D, tp, pp);
             std::vector<Piece> pieces;
             for (const Rect& d : col.rects) {
                 const i64 dw = d.c1 - d.c0;

@@ -51,17 +51,31 @@ def vocab_rows(spec, TP, vm=0):
     return V // TP if not vm else (V + vm * TP - 1) // (vm * TP) * vm
 
 
-def stage_param_sizes(spec, TP, PP, pp, vpp=1, vm=0):
+def uneven_stage_range(L, PP, pp, first, last):
+    """[lo, hi) of the layers of stage pp when the first / last stage hold `first` / `last` layers
+    (0 = not fixed) and the remaining stages share the rest evenly."""
+    n_other = PP - (first > 0) - (last > 0)
+    per = (L - first - last) // n_other if n_other else 0
+    count = lambda p: first if (p == 0 and first) else last if (p == PP - 1 and last) else per
+    lo = sum(count(p) for p in range(pp))
+    return lo, lo + count(pp)
+
+
+def stage_param_sizes(spec, TP, PP, pp, vpp=1, vm=0, first=0, last=0):
     H, hd, Q, KV, F, V = dims(spec)
     out = []
     if pp == 0:
         out.append(("embed.word", vocab_rows(spec, TP, vm) * H))
         if spec.max_pos:
             out.append(("embed.pos", spec.max_pos * H))
-    c = spec.n_layers // (PP * vpp)         # layers per model chunk; stage pp holds chunks pp, pp+PP, ...
+    if first or last:
+        for l in range(*uneven_stage_range(spec.n_layers, PP, pp, first, last)):
+            out += layer_param_sizes(spec, TP, l)
+        vpp = 0
+    c = spec.n_layers // (PP * max(vpp, 1))  # layers per model chunk; stage pp holds chunks pp, pp+PP, ...
     for v in range(vpp):
-        first = (v * PP + pp) * c
-        for l in range(first, first + c):
+        lo = (v * PP + pp) * c
+        for l in range(lo, lo + c):
             out += layer_param_sizes(spec, TP, l)
     if pp == PP - 1:
         out.append(("final_norm.w", H))
@@ -74,13 +88,13 @@ def stage_param_sizes(spec, TP, PP, pp, vpp=1, vm=0):
     return out
 
 
-def n_local(spec, TP, PP, pp, vpp=1, vm=0):
-    return sum(n for _, n in stage_param_sizes(spec, TP, PP, pp, vpp, vm))
+def n_local(spec, TP, PP, pp, vpp=1, vm=0, first=0, last=0):
+    return sum(n for _, n in stage_param_sizes(spec, TP, PP, pp, vpp, vm, first, last))
 
 
-def n_pad(spec, TP, PP, DP, pad_multiple, pp, vpp=1, vm=0):
+def n_pad(spec, TP, PP, DP, pad_multiple, pp, vpp=1, vm=0, first=0, last=0):
     q = DP * pad_multiple
-    return (n_local(spec, TP, PP, pp, vpp, vm) + q - 1) // q * q
+    return (n_local(spec, TP, PP, pp, vpp, vm, first, last) + q - 1) // q * q
 
 
 def owner(spec, TP, tp, phys, k, vm=0):
@@ -151,14 +165,14 @@ def owner(spec, TP, tp, phys, k, vm=0):
     raise KeyError(phys)
 
 
-def column_ownership(spec, TP, PP, tp, pp, vpp=1, vm=0):
+def column_ownership(spec, TP, PP, tp, pp, vpp=1, vm=0, first=0, last=0):
     """For flat offsets 0..N_local-1 of rank column (tp, pp): (names, idx, canonical).
     names[k] is None where the element is vocabulary padding.
 
     canonical[k] is False where the element is a replica that a gather must not
     read: TP-replicated parameters on tp > 0 and the tied-embedding copy."""
     names, idx, canon = [], [], []
-    for phys, n in stage_param_sizes(spec, TP, PP, pp, vpp, vm):
+    for phys, n in stage_param_sizes(spec, TP, PP, pp, vpp, vm, first, last):
         nm, ix = owner(spec, TP, tp, phys, np.arange(n, dtype=np.int64), vm)
         names.append(nm)
         idx.append(ix)

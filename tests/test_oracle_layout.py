@@ -24,13 +24,14 @@ SPECS = {
     "odd_vocab_tied": oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=4, n_kv_heads=4, ffn=32, vocab=50,
                                        max_pos=8, tied_embed=True),
     "odd_vocab_head": oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=4, n_kv_heads=4, ffn=32, vocab=37, glu=True),
-    "mqa_tied": oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=4, n_kv_heads=1, ffn=64, vocab=32,
+    "mqa_tied": oracle.ModelSpec(n_layers=4, hidden=32, n_q_heads=4, n_kv_heads=1, ffn=64, vocab=32,
                                  tied_embed=True),
 }
 LAYOUTS = [(1, 1, 1, 128), (2, 1, 2, 128), (1, 2, 2, 128), (2, 2, 3, 4), (4, 2, 1, 1), (2, 1, 3, 1),
            (2, 2, 2, 4, 2), (1, 1, 1, 1, 2), (1, 2, 3, 1, 1),       # 5th entry: vpp (interleaved stages)
            (8, 1, 2, 4),                                            # TP 8 > n_kv: replicated kv heads
-           (2, 2, 2, 4, 1, 8), (4, 1, 1, 1, 1, 4), (1, 1, 2, 1, 1, 16), (4, 2, 3, 128, 1, 32)]   # 6th: vocab_multiple
+           (2, 2, 2, 4, 1, 8), (4, 1, 1, 1, 1, 4), (1, 1, 2, 1, 1, 16), (4, 2, 3, 128, 1, 32),   # 6th: vocab_multiple
+           (1, 2, 2, 4, 1, 0, 1, 0), (2, 2, 1, 1, 1, 0, 3, 1), (1, 3, 1, 1, 1, 0, 1, 1)]         # 7th, 8th: pp_first, pp_last
 
 
 def _cases():
@@ -61,10 +62,10 @@ def test_split_matches_ownership(spec, lay):
     w_hi = make_world(spec, lay, synth.index_encoded_state(shapes, half=1), poison=False)
     w_ord = make_world(spec, lay, _tensor_ordinal_state(spec), poison=False)
     for pp in range(lay.pp):
-        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp, lay.vocab_multiple)
+        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last)
         S = npad // lay.dp
         for tp in range(lay.tp):
-            names, idx, _ = own.column_ownership(spec, lay.tp, lay.pp, tp, pp, lay.vpp, lay.vocab_multiple)
+            names, idx, _ = own.column_ownership(spec, lay.tp, lay.pp, tp, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last)
             nl = len(names)
             exp_idx = np.zeros(npad, np.int64)
             exp_idx[:nl] = idx
@@ -155,3 +156,22 @@ def test_padded_vocab_sizes():
         assert sum(b.loc[0].stop - b.loc[0].start for b in emb.blocks) == real
     with pytest.raises(ValueError):
         oracle.stage_view(spec, oracle.Layout(2, 1, 1, 128), 0, 0)        # 50257 % 2 != 0 and no padding
+
+
+def test_uneven_stage_layers():
+    """Fixed layer counts on the first / last stage, the rest shared evenly."""
+    spec = oracle.ModelSpec(n_layers=10, hidden=32, n_q_heads=4, n_kv_heads=4, ffn=64, vocab=32)
+    L = lambda *a: oracle.Layout(1, a[0], 1, 1, 1, 0, a[1], a[2])
+    assert [oracle.stage_layers(spec, L(4, 1, 3), p) for p in range(4)] == [[0], [1, 2, 3], [4, 5, 6], [7, 8, 9]]
+    assert [oracle.stage_layers(spec, L(3, 2, 0), p) for p in range(3)] == [[0, 1], [2, 3, 4, 5], [6, 7, 8, 9]]
+    assert [oracle.stage_layers(spec, L(2, 7, 3), p) for p in range(2)] == [list(range(7)), [7, 8, 9]]
+    assert [oracle.stage_layers(spec, L(3, 0, 4), p) for p in range(3)] == [[0, 1, 2], [3, 4, 5], [6, 7, 8, 9]]
+    for bad in (L(4, 1, 2), L(2, 7, 2), L(3, 9, 1), L(2, 10, 0)):          # 7 over 2 stages; 7+2 != 10; nothing left; empty stage
+        with pytest.raises(ValueError):
+            oracle.stage_view(spec, bad, 0, 0)
+    with pytest.raises(ValueError):
+        oracle.stage_view(spec, oracle.Layout(1, 5, 1, 1, 2, 0, 2, 0), 0, 0)   # not combinable with vpp
+    for lay in (L(4, 1, 3), L(3, 0, 4)):
+        for p in range(lay.pp):
+            assert own.uneven_stage_range(10, lay.pp, p, lay.pp_first, lay.pp_last) == \
+                (oracle.stage_layers(spec, lay, p)[0], oracle.stage_layers(spec, lay, p)[-1] + 1)

@@ -42,6 +42,8 @@ BRUTE = [
     (VOC, (1, 2, 1, 1, 1, 0), (4, 1, 3, 4, 1, 16)),  # unpadded 50 -> padded 64, tied copy dropped (corrupted pads)
     (VOCH, (2, 1, 3, 1, 1, 5), (1, 2, 2, 128, 1, 3)),   # 40 -> 39 rows, untied head
     (VOCH, (1, 1, 1, 1, 1, 64), (4, 2, 1, 1, 1, 16)),   # tp 3 holds rows 48..63: all padding (and kv heads replicated)
+    (ODD6, (2, 3, 1, 4), (1, 3, 2, 1, 1, 0, 1, 3)),     # even stages -> 1 / 2 / 3 layers (7th, 8th = pp_first, pp_last)
+    (ODD6, (3, 2, 2, 1, 1, 0, 5, 0), (2, 4, 1, 4, 1, 0, 0, 3)),   # 5 / 1 -> 1 / 1 / 1 / 3
 ]
 
 

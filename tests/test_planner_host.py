@@ -214,6 +214,10 @@ def test_error_codes():
     with pytest.raises(lv.LiverError) as e:
         lv.liver_plan_create(s, lv.Layout(2, 1, 2, only_tp=0), b, 4096)
     assert e.value.code == -2
+    for bad in (lv.Layout(1, 2, 2, pp_first=3), lv.Layout(1, 2, 2, vpp=2), lv.Layout(1, 2, 2, pp_first=1, vpp=1, pp_last=2),
+                lv.Layout(8, 1, 1), lv.Layout(1, 1, 1, vocab_multiple=-1)):
+        with pytest.raises(lv.LiverError):          # 2 layers: 3 on the first stage; 4 chunks; 1+2; 4 heads over TP 8
+            lv.liver_plan_create(s, a, bad, 4096)
     plan = lv.liver_plan_create(s, a, b, 4096)
     with pytest.raises(lv.LiverError):
         lv.liver_plan_buffer_bytes(plan, 0, 99, 0)

@@ -20,8 +20,8 @@ def poison_pads(spec, lay, bufs):
     """Overwrite the padding of every buffer of world `lay` with NaN sentinels
     (source padding must never be read by a reshard)."""
     for pp in range(lay.pp):
-        nl = own.n_local(spec, lay.tp, lay.pp, pp, lay.vpp, lay.vocab_multiple)
-        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp, lay.vocab_multiple)
+        nl = own.n_local(spec, lay.tp, lay.pp, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last)
+        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last)
         S = npad // lay.dp
         for tp in range(lay.tp):
             for dp in range(lay.dp):
@@ -48,10 +48,10 @@ def corrupt_replicas(spec, lay, bufs):
     formulas (not by the oracle): TP-replicated parameters on tp > 0, the tied
     embedding copy, PARAM replicas with dp > 0, and vocabulary padding rows."""
     for pp in range(lay.pp):
-        nl = own.n_local(spec, lay.tp, lay.pp, pp, lay.vpp, lay.vocab_multiple)
-        S = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp, lay.vocab_multiple) // lay.dp
+        nl = own.n_local(spec, lay.tp, lay.pp, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last)
+        S = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last) // lay.dp
         for tp in range(lay.tp):
-            names, _, canon = own.column_ownership(spec, lay.tp, lay.pp, tp, pp, lay.vpp, lay.vocab_multiple)
+            names, _, canon = own.column_ownership(spec, lay.tp, lay.pp, tp, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last)
             bad = np.flatnonzero(~canon | np.equal(names, None))       # copies, and vocabulary padding
             for dp in range(lay.dp):
                 r = lay.rank(tp, pp, dp)
@@ -81,10 +81,10 @@ def brute_reshard(spec, src, dst, src_bufs, derive=False):
     alone (tiny models only).  Independent of the oracle's slicing."""
     value = {k: {} for k in oracle.KINDS}
     for pp in range(src.pp):
-        npad = own.n_pad(spec, src.tp, src.pp, src.dp, src.pad_multiple, pp, src.vpp, src.vocab_multiple)
+        npad = own.n_pad(spec, src.tp, src.pp, src.dp, src.pad_multiple, pp, src.vpp, src.vocab_multiple, src.pp_first, src.pp_last)
         S = npad // src.dp
         for tp in range(src.tp):
-            names, idx, canon = own.column_ownership(spec, src.tp, src.pp, tp, pp, src.vpp, src.vocab_multiple)
+            names, idx, canon = own.column_ownership(spec, src.tp, src.pp, tp, pp, src.vpp, src.vocab_multiple, src.pp_first, src.pp_last)
             for k in range(len(names)):
                 if not canon[k] or names[k] is None:
                     continue
@@ -98,10 +98,10 @@ def brute_reshard(spec, src, dst, src_bufs, derive=False):
         value[oracle.PARAM] = {key: _rne_scalar(int(v)) for key, v in value[oracle.MASTER].items()}
     out = {}
     for pp in range(dst.pp):
-        npad = own.n_pad(spec, dst.tp, dst.pp, dst.dp, dst.pad_multiple, pp, dst.vpp, dst.vocab_multiple)
+        npad = own.n_pad(spec, dst.tp, dst.pp, dst.dp, dst.pad_multiple, pp, dst.vpp, dst.vocab_multiple, dst.pp_first, dst.pp_last)
         S = npad // dst.dp
         for tp in range(dst.tp):
-            names, idx, _ = own.column_ownership(spec, dst.tp, dst.pp, tp, pp, dst.vpp, dst.vocab_multiple)
+            names, idx, _ = own.column_ownership(spec, dst.tp, dst.pp, tp, pp, dst.vpp, dst.vocab_multiple, dst.pp_first, dst.pp_last)
             flat = {kind: np.zeros(npad, oracle.WORD[kind]) for kind in oracle.KINDS}
             for k in range(len(names)):
                 if names[k] is None:            # vocabulary padding stays +0
