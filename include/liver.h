@@ -52,7 +52,9 @@
  *     elements.  LIVER_PARAM_BF16 holds all N_pad elements on every DP rank;
  *     LIVER_MASTER_F32 / LIVER_ADAM_M_F32 / LIVER_ADAM_V_F32 are split evenly:
  *     DP rank d holds elements [d*S, (d+1)*S), S = N_pad/DP (distributed
- *     optimizer);
+ *     optimizer).  With bucket_elems > 0 this holds per bucket (see
+ *     liver_layout_t): padding sits at the end of every bucket and a DP rank
+ *     holds the d-th DP-th of every bucket, concatenated;
  *   - a value that exists several times in the source world is read from the
  *     copy with the lowest coordinate (dp = 0, tp = 0, first stage); source
  *     padding is never read; target padding is written +0.
@@ -118,6 +120,12 @@ typedef struct {
     int32_t pp_first, pp_last;          /* > 0: number of layers on the first / last pipeline stage; the
                                            other stages share the remaining layers evenly.  0 = even
                                            split.  Not combinable with vpp > 1 */
+    int64_t bucket_elems;               /* > 0: the flat buffer is a sequence of buckets: parameters are
+                                           appended in order and a bucket closes after the parameter that
+                                           brings it to >= bucket_elems elements; EVERY bucket is padded
+                                           to a multiple of dp*pad_multiple and split evenly over DP, and
+                                           a DP rank's fp32 buffer is the concatenation of its slices.
+                                           0 = one bucket */
 } liver_layout_t;
 
 typedef struct {

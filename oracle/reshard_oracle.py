@@ -34,9 +34,15 @@ Megatron-style mixed-parallel training, stated so a reader can check it by eye):
   R5  a (tp, pp) rank's parameters are flattened row-major and packed back to
       back, in forward order, into one flat buffer; the bf16 and fp32 buffers
       use the same element offsets.
-  R6  the flat buffer is zero-padded to N_pad, a multiple of DP*pad_multiple;
-      PARAM (bf16) is a full N_pad copy on every DP rank; MASTER / ADAM_M /
-      ADAM_V (fp32) are split evenly: DP rank d owns [d*S, (d+1)*S), S=N_pad/DP.
+  R5b with bucket_elems = B > 0 the flat buffer is a sequence of BUCKETS (as a
+      distributed optimizer's gradient / parameter buffer is): parameters are
+      appended in order and a bucket closes after the parameter that brings it
+      to >= B elements; the last bucket takes the rest.  B = 0: one bucket.
+  R6  every bucket is zero-padded to a multiple of DP*pad_multiple elements (the
+      flat buffer then has N_pad elements).  PARAM (bf16) is a full N_pad copy on
+      every DP rank; MASTER / ADAM_M / ADAM_V (fp32) are split evenly PER BUCKET:
+      DP rank d owns the d-th DP-th of every bucket and its buffer is the
+      concatenation of those slices (one bucket: [d*S, (d+1)*S), S = N_pad/DP).
   R7  where a value exists more than once in the source world, the copy that is
       read is the one with the lowest coordinate (dp=0, tp=0, first stage).
   R8  with tied embeddings and PP>1 the last stage holds a second physical copy
@@ -103,6 +109,7 @@ class Layout:
     vocab_multiple: int = 0   # R11b: pad the vocabulary to a multiple of vocab_multiple*TP rows; 0 = no padding
     pp_first: int = 0         # R9c: layers on the first / last stage (0 = even share); the other
     pp_last: int = 0          #      stages split the remaining layers evenly
+    bucket_elems: int = 0     # R5b: flat buffer cut into buckets of at least this many elements (0 = one bucket)
 
     @property
     def n_ranks(self) -> int:
@@ -205,9 +212,10 @@ class PhysParam:
 @dataclass
 class StageView:
     params: List[PhysParam]
-    n_local: int
+    n_local: int              # end of the last parameter (interior bucket padding included)
     n_pad: int
-    S: int                    # elements per DP slice of the fp32 buffers
+    S: int                    # elements of one DP rank's fp32 buffers = N_pad / DP
+    buckets: List[Tuple[int, int]] = field(default_factory=list)   # (start, padded size) in flat coordinates
 
 
 def _rows(a: int, b: int) -> Tuple[slice, ...]:
@@ -342,13 +350,17 @@ def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int) -> StageView:
         elif lay.pp > 1:                             # R8: second copy, never the one read
             vocab_split("embed.word(tied copy)", "embed.word", canonical=False)
 
-    off = 0
-    for prm in out:                                  # R5: back to back, no per-param padding
-        prm.offset = off
-        off += prm.size
     quantum = lay.dp * lay.pad_multiple              # R6
-    n_pad = -(-off // quantum) * quantum
-    return StageView(out, off, n_pad, n_pad // lay.dp)
+    buckets: List[Tuple[int, int]] = []
+    off = start = end = 0
+    for i, prm in enumerate(out):                    # R5: back to back, no per-param padding
+        prm.offset = off
+        off = end = off + prm.size
+        if (lay.bucket_elems and off - start >= lay.bucket_elems) or i == len(out) - 1:     # R5b: bucket closes
+            off = start + -(-(off - start) // quantum) * quantum
+            buckets.append((start, off - start))
+            start = off
+    return StageView(out, end, off, off // lay.dp, buckets)
 
 
 def buffer_elems(spec: ModelSpec, lay: Layout, tp: int, pp: int, kind: int) -> int:
@@ -364,19 +376,31 @@ def dict_reader(bufs: Dict[Tuple[int, int], np.ndarray]) -> Reader:
     return lambda rank, kind, lo, hi: bufs[(rank, kind)][lo:hi]
 
 
-def read_flat(read: Reader, lay: Layout, tp: int, pp: int, kind: int, lo: int, hi: int, S: int,
+def dp_pieces(sv: StageView, lay: Layout, lo: int, hi: int) -> List[Tuple[int, int, int, int]]:
+    """Where flat elements [lo, hi) of a rank column live in the fp32 buffers (R6):
+    [(dp rank, offset in that rank's buffer, flat offset, count)] in flat order.
+    Each bucket is cut into DP equal slices; a rank's buffer is the concatenation
+    of its slice of every bucket."""
+    out, prefix = [], 0
+    for b0, nb in sv.buckets:
+        sb = nb // lay.dp
+        for d in range(lay.dp):
+            a, b = max(lo, b0 + d * sb), min(hi, b0 + (d + 1) * sb)
+            if a < b:
+                out.append((d, prefix + a - b0 - d * sb, a, b - a))
+        prefix += sb
+    return out
+
+
+def read_flat(read: Reader, lay: Layout, sv: StageView, tp: int, pp: int, kind: int, lo: int, hi: int,
               dp_replica: int = 0) -> np.ndarray:
-    """Elements [lo, hi) of the (tp, pp) flat buffer of `kind` -- R6.
+    """Elements [lo, hi) of the (tp, pp) flat buffer of `kind`.
 
     PARAM: taken from replica `dp_replica`.  fp32 kinds: concatenation of the
-    pieces held by the DP ranks whose slices [d*S, (d+1)*S) overlap [lo, hi)."""
+    pieces held by the DP ranks (dp_pieces)."""
     if kind == PARAM:
         return np.asarray(read(lay.rank(tp, pp, dp_replica), kind, lo, hi))
-    parts = []
-    for d in range(lay.dp):
-        a, b = max(lo, d * S), min(hi, (d + 1) * S)
-        if a < b:
-            parts.append(np.asarray(read(lay.rank(tp, pp, d), kind, a - d * S, b - d * S)))
+    parts = [np.asarray(read(lay.rank(tp, pp, d), kind, loc, loc + n)) for d, loc, _, n in dp_pieces(sv, lay, lo, hi)]
     return np.concatenate(parts) if parts else np.empty(0, WORD[kind])
 
 
@@ -399,8 +423,7 @@ def gather_logical(spec: ModelSpec, lay: Layout, kind: int, read: Reader,
             for prm in sv.params:
                 if not prm.canonical or not any(b.name in want and b.canonical for b in prm.blocks):
                     continue
-                local = read_flat(read, lay, tp, pp, kind, prm.offset, prm.offset + prm.size,
-                                  sv.S).reshape(prm.shape)
+                local = read_flat(read, lay, sv, tp, pp, kind, prm.offset, prm.offset + prm.size).reshape(prm.shape)
                 for b in prm.blocks:
                     if b.name in want and b.canonical:
                         logical[b.name][b.idx] = local[b.loc]
@@ -436,8 +459,9 @@ def split_logical(spec: ModelSpec, lay: Layout, kind: int,
             for dp in range(lay.dp):
                 if kind == PARAM:
                     out[(lay.rank(tp, pp, dp), kind)] = flat.copy()
-                else:
-                    out[(lay.rank(tp, pp, dp), kind)] = flat[dp * sv.S:(dp + 1) * sv.S].copy()
+                else:                                # this rank's slice of every bucket, concatenated
+                    out[(lay.rank(tp, pp, dp), kind)] = np.concatenate(
+                        [flat[b0 + dp * (nb // lay.dp):b0 + (dp + 1) * (nb // lay.dp)] for b0, nb in sv.buckets])
     return out
 
 
@@ -489,5 +513,5 @@ def expected_shards(spec: ModelSpec, lay: Layout, logical: Dict[str, np.ndarray]
 
 __all__ = ["PARAM", "MASTER", "ADAM_M", "ADAM_V", "KINDS", "WORD", "ModelSpec", "Layout",
            "check_supported", "padded_vocab", "logical_tensors", "Block", "PhysParam", "StageView", "stage_layers", "stage_view",
-           "buffer_elems", "Reader", "dict_reader", "read_flat", "gather_logical", "build_shard",
+           "buffer_elems", "Reader", "dict_reader", "dp_pieces", "read_flat", "gather_logical", "build_shard",
            "split_logical", "rne_bf16", "reshard_state", "expected_shards"]

@@ -44,7 +44,7 @@ class _Spec(C.Structure):
 
 class _Layout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("tp", "pp", "dp", "pad_multiple", "only_tp", "only_pp", "only_dp")] \
-        + [("flags", C.c_uint32), ("kind_mask", C.c_uint32), ("vpp", C.c_int32), ("vocab_multiple", C.c_int32), ("pp_first", C.c_int32), ("pp_last", C.c_int32)]
+        + [("flags", C.c_uint32), ("kind_mask", C.c_uint32), ("vpp", C.c_int32), ("vocab_multiple", C.c_int32), ("pp_first", C.c_int32), ("pp_last", C.c_int32), ("bucket_elems", C.c_int64)]
 
 
 class PlanInfo(C.Structure):
@@ -95,6 +95,7 @@ class Layout:
     vocab_multiple: int = 0                      # pad the vocabulary to a multiple of vocab_multiple*tp rows
     pp_first: int = 0                            # layers on the first / last stage (0 = even split)
     pp_last: int = 0
+    bucket_elems: int = 0                        # flat buffer cut into buckets of >= this many elements (0 = one)
 
     @property
     def n_ranks(self) -> int:
@@ -106,7 +107,7 @@ class Layout:
     def _c(self) -> _Layout:
         mask = 0 if self.kinds is None else sum(1 << k for k in set(self.kinds))
         return _Layout(self.tp, self.pp, self.dp, self.pad_multiple, self.only_tp, self.only_pp, self.only_dp,
-                       _DERIVE * self.derive_bf16, mask, self.vpp, self.vocab_multiple, self.pp_first, self.pp_last)
+                       _DERIVE * self.derive_bf16, mask, self.vpp, self.vocab_multiple, self.pp_first, self.pp_last, self.bucket_elems)
 
 
 def _load() -> C.CDLL:

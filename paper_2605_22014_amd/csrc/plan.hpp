@@ -70,8 +70,16 @@ struct List {
     int64_t hbm_read = 0, hbm_written = 0;  // bytes the lowered descriptors read / write
 };
 
+struct Bucket {
+    int64_t start = 0, padded = 0;  // flat offset and padded size
+    int64_t slice = 0;              // padded / DP: what one DP rank holds of it
+    int64_t prefix = 0;             // sum of the slices of the buckets before it = offset in a DP rank's buffer
+};
+
 struct StageSize {
-    int64_t n_local = 0, n_pad = 0, S = 0;
+    int64_t n_local = 0, n_pad = 0, S = 0;  // end of the last parameter, padded size, N_pad / DP
+    std::vector<Bucket> buckets;            // the flat buffer is a sequence of buckets (at least one)
+    std::vector<int64_t> bounds;            // sorted flat offsets where the owning (bucket, DP rank) changes
 };
 
 }  // namespace liver

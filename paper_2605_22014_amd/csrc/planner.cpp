@@ -49,8 +49,9 @@ struct ZeroRegion {  // flat elements [off, off + n) of a rank column that hold 
 struct Column {
     int tp = 0, pp = 0;
     std::vector<Rect> rects;
-    std::vector<ZeroRegion> zeros;  // vocabulary padding rows inside the buffer (the tail pad is added later)
-    i64 n_local = 0;
+    std::vector<ZeroRegion> zeros;            // every padding region: vocabulary padding rows, bucket padding
+    std::vector<std::pair<i64, i64>> buckets;  // (start, padded size) of each bucket
+    i64 n_local = 0, n_pad = 0;                // end of the last parameter; total padded size
     int last_slot = 0;
 };
 
@@ -87,11 +88,28 @@ Column build_column(const Geo& g, const liver_layout_t& lay, int tp, int pp) {
     Column col;
     col.tp = tp;
     col.pp = pp;
-    i64 off = 0;
-    auto add = [&](int tensor, int slot, i64 r0, i64 r1, i64 c0, i64 c1, bool canonical) {
+    i64 off = 0, bucket_start = 0, params_in_bucket = 0;
+    const i64 quantum = (i64)lay.dp * lay.pad_multiple;
+    // A bucket is zero-padded to a multiple of DP*pad_multiple elements when it closes.
+    auto close_bucket = [&]() {
+        const i64 used = off - bucket_start, padded = (used + quantum - 1) / quantum * quantum;
+        if (padded > used) col.zeros.push_back({col.last_slot, off, padded - used});
+        col.buckets.push_back({bucket_start, padded});
+        off = bucket_start = bucket_start + padded;
+        params_in_bucket = 0;
+    };
+    // Called after the last rectangle of every physical parameter: with bucket_elems > 0 the bucket closes
+    // after the parameter that brings it to at least that many elements.
+    auto end_param = [&]() {
+        col.n_local = off;
+        ++params_in_bucket;
+        if (lay.bucket_elems > 0 && off - bucket_start >= lay.bucket_elems) close_bucket();
+    };
+    auto add = [&](int tensor, int slot, i64 r0, i64 r1, i64 c0, i64 c1, bool canonical, bool end = true) {
         col.rects.push_back({tensor, slot, r0, r1, c0, c1, off, canonical});
         off += (r1 - r0) * (c1 - c0);
         col.last_slot = slot;
+        if (end) end_param();
     };
     const bool lead = (tp == 0);  // TP-replicated parameters are read from tp 0
     const i64 g_loc = g.nkv / TP, fn = g.F / TP, qn = g.Q / TP;
@@ -104,6 +122,7 @@ Column build_column(const Geo& g, const liver_layout_t& lay, int tp, int pp) {
         if (real < vn * g.H) col.zeros.push_back({slot, off + real, vn * g.H - real});
         off += vn * g.H;
         col.last_slot = slot;
+        end_param();
     };
     if (pp == 0) {
         add_vocab(T_EMBED_WORD, 0, true);
@@ -119,36 +138,36 @@ Column build_column(const Geo& g, const liver_layout_t& lay, int tp, int pp) {
         const i64 rep = g_loc == 0 ? TP / g.nkv : 1, part = tp % rep, nq = g.qpg / rep * g.hd;
         if (g_loc == 0) {
             const i64 gi = tp / rep;
-            add(b + Q_W, slot, gi * g.qpg * g.hd + part * nq, gi * g.qpg * g.hd + (part + 1) * nq, 0, g.H, true);
-            add(b + K_W, slot, gi * g.hd, (gi + 1) * g.hd, 0, g.H, part == 0);
+            add(b + Q_W, slot, gi * g.qpg * g.hd + part * nq, gi * g.qpg * g.hd + (part + 1) * nq, 0, g.H, true, false);
+            add(b + K_W, slot, gi * g.hd, (gi + 1) * g.hd, 0, g.H, part == 0, false);
             add(b + V_W, slot, gi * g.hd, (gi + 1) * g.hd, 0, g.H, part == 0);
             if (g.lin_bias) {
-                add(b + Q_B, slot, 0, 1, gi * g.qpg * g.hd + part * nq, gi * g.qpg * g.hd + (part + 1) * nq, true);
-                add(b + K_B, slot, 0, 1, gi * g.hd, (gi + 1) * g.hd, part == 0);
+                add(b + Q_B, slot, 0, 1, gi * g.qpg * g.hd + part * nq, gi * g.qpg * g.hd + (part + 1) * nq, true, false);
+                add(b + K_B, slot, 0, 1, gi * g.hd, (gi + 1) * g.hd, part == 0, false);
                 add(b + V_B, slot, 0, 1, gi * g.hd, (gi + 1) * g.hd, part == 0);
             }
         }
         for (i64 j = 0; j < g_loc; ++j) {  // fused qkv weight: [q of group ; k ; v] per kv group
             const i64 gi = tp * g_loc + j;
-            add(b + Q_W, slot, gi * g.qpg * g.hd, (gi + 1) * g.qpg * g.hd, 0, g.H, true);
-            add(b + K_W, slot, gi * g.hd, (gi + 1) * g.hd, 0, g.H, true);
-            add(b + V_W, slot, gi * g.hd, (gi + 1) * g.hd, 0, g.H, true);
+            add(b + Q_W, slot, gi * g.qpg * g.hd, (gi + 1) * g.qpg * g.hd, 0, g.H, true, false);
+            add(b + K_W, slot, gi * g.hd, (gi + 1) * g.hd, 0, g.H, true, false);
+            add(b + V_W, slot, gi * g.hd, (gi + 1) * g.hd, 0, g.H, true, j == g_loc - 1);
         }
         if (g.lin_bias)
             for (i64 j = 0; j < g_loc; ++j) {
                 const i64 gi = tp * g_loc + j;
-                add(b + Q_B, slot, 0, 1, gi * g.qpg * g.hd, (gi + 1) * g.qpg * g.hd, true);
-                add(b + K_B, slot, 0, 1, gi * g.hd, (gi + 1) * g.hd, true);
-                add(b + V_B, slot, 0, 1, gi * g.hd, (gi + 1) * g.hd, true);
+                add(b + Q_B, slot, 0, 1, gi * g.qpg * g.hd, (gi + 1) * g.qpg * g.hd, true, false);
+                add(b + K_B, slot, 0, 1, gi * g.hd, (gi + 1) * g.hd, true, false);
+                add(b + V_B, slot, 0, 1, gi * g.hd, (gi + 1) * g.hd, true, j == g_loc - 1);
             }
         add(b + O_W, slot, 0, g.H, tp * qn, (tp + 1) * qn, true);  // row-parallel: a strip of every row
         if (g.lin_bias) add(b + O_B, slot, 0, 1, 0, g.H, lead);
         add(b + LN2_W, slot, 0, 1, 0, g.H, lead);
         if (g.norm_bias) add(b + LN2_B, slot, 0, 1, 0, g.H, lead);
-        if (g.glu) add(b + GATE_W, slot, tp * fn, (tp + 1) * fn, 0, g.H, true);
+        if (g.glu) add(b + GATE_W, slot, tp * fn, (tp + 1) * fn, 0, g.H, true, false);
         add(b + UP_W, slot, tp * fn, (tp + 1) * fn, 0, g.H, true);
         if (g.lin_bias) {
-            if (g.glu) add(b + GATE_B, slot, 0, 1, tp * fn, (tp + 1) * fn, true);
+            if (g.glu) add(b + GATE_B, slot, 0, 1, tp * fn, (tp + 1) * fn, true, false);
             add(b + UP_B, slot, 0, 1, tp * fn, (tp + 1) * fn, true);
         }
         add(b + DOWN_W, slot, 0, g.H, tp * fn, (tp + 1) * fn, true);
@@ -163,7 +182,8 @@ Column build_column(const Geo& g, const liver_layout_t& lay, int tp, int pp) {
         else if (PP > 1)  // second copy of the tied embedding: written, never read
             add_vocab(T_EMBED_WORD, slot, false);
     }
-    col.n_local = off;
+    if (params_in_bucket > 0 || col.buckets.empty()) close_bucket();  // the last bucket takes what is left
+    col.n_pad = off;
     return col;
 }
 
@@ -220,11 +240,12 @@ void slice(const Entry& e, i64 p0, i64 p1, std::vector<Entry>& out) {
     if (c1 > 0) sub(r1, 0, 1, c1);
 }
 
-// Payload positions at which the piece (off, stride, rows, run) crosses a
-// multiple of S in flat-buffer coordinates.
-void boundary_cuts(i64 off, i64 stride, i64 rows, i64 run, i64 S, std::vector<i64>& cuts) {
+// Payload positions at which the piece (off, stride, rows, run) crosses one of the sorted flat-buffer
+// boundaries `bounds` (where the owning bucket or DP rank changes).
+void boundary_cuts(i64 off, i64 stride, i64 rows, i64 run, const std::vector<i64>& bounds, std::vector<i64>& cuts) {
     const i64 end = off + (rows - 1) * stride + run;  // one past the last element
-    for (i64 b = (off / S + 1) * S; b < end; b += S) {
+    for (auto it = std::upper_bound(bounds.begin(), bounds.end(), off); it != bounds.end() && *it < end; ++it) {
+        const i64 b = *it;
         if (rows == 1) {
             cuts.push_back(b - off);
             continue;
@@ -235,6 +256,19 @@ void boundary_cuts(i64 off, i64 stride, i64 rows, i64 run, i64 S, std::vector<i6
         const i64 start = off + i * stride;
         cuts.push_back(start >= b ? i * run : i * run + (b - start));
     }
+}
+
+// Flat offset -> (DP rank, offset in that rank's fp32 buffer).
+void locate(const StageSize& st, i64 flat, int& dp, i64& local) {
+    size_t lo = 0, hi = st.buckets.size();
+    while (hi - lo > 1) {
+        const size_t mid = (lo + hi) / 2;
+        if (st.buckets[mid].start <= flat) lo = mid;
+        else hi = mid;
+    }
+    const Bucket& b = st.buckets[lo];
+    dp = (int)((flat - b.start) / b.slice);
+    local = b.prefix + (flat - b.start) - dp * b.slice;
 }
 
 struct Builder {
@@ -278,11 +312,11 @@ struct Builder {
         }
         const bool any_f32 = kind_on(LIVER_MASTER_F32) || kind_on(LIVER_ADAM_M_F32) || kind_on(LIVER_ADAM_V_F32);
         if (!any_f32 && !(derive && kind_on(LIVER_PARAM_BF16))) return;
-        // cut at source and target DP slice boundaries
-        const i64 Ss = plan.src_stage[s_pp].S, Sd = plan.dst_stage[d_pp].S;
+        // cut where the owning bucket / DP rank changes, on the source and on the target side
+        const StageSize &sst = plan.src_stage[s_pp], &dst_st = plan.dst_stage[d_pp];
         std::vector<i64> cuts{0, rows * run};
-        boundary_cuts(s_off, s_stride, rows, run, Ss, cuts);
-        boundary_cuts(d_off, d_stride, rows, run, Sd, cuts);
+        boundary_cuts(s_off, s_stride, rows, run, sst.bounds, cuts);
+        boundary_cuts(d_off, d_stride, rows, run, dst_st.bounds, cuts);
         std::sort(cuts.begin(), cuts.end());
         cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
         Entry flat;
@@ -293,8 +327,10 @@ struct Builder {
         std::vector<Entry> parts;
         for (size_t c = 0; c + 1 < cuts.size(); ++c) slice(flat, cuts[c], cuts[c + 1], parts);
         for (const Entry& p : parts) {
-            const int sdp = int(p.src_off / Ss), ddp = int(p.dsts[0].off / Sd);
-            const i64 s_local = p.src_off - sdp * Ss, d_local = p.dsts[0].off - ddp * Sd;
+            int sdp, ddp;
+            i64 s_local, d_local;
+            locate(sst, p.src_off, sdp, s_local);
+            locate(dst_st, p.dsts[0].off, ddp, d_local);
             for (int k = LIVER_MASTER_F32; k <= LIVER_ADAM_V_F32; ++k) {
                 Entry e;
                 e.slot = slot;
@@ -316,28 +352,36 @@ struct Builder {
     void zero_padding(const Column& col) {
         const liver_layout_t& D = plan.dst;
         const StageSize& st = plan.dst_stage[col.pp];
-        std::vector<ZeroRegion> regions = col.zeros;  // vocabulary padding rows ...
-        if (st.n_pad > st.n_local) regions.push_back({col.last_slot, st.n_local, st.n_pad - st.n_local});  // ... and the tail
-        for (const ZeroRegion& z : regions)
-            for (int dp = 0; dp < D.dp; ++dp) {
-                if (!dst_dp_planned(dp)) continue;
-                const int rank = rank_of(D, col.tp, col.pp, dp);
-                for (int k = 0; k < LIVER_NUM_KINDS; ++k) {
-                    if (!kind_on(k)) continue;
-                    i64 lo = z.off, hi = z.off + z.n, base = 0;
-                    if (k != LIVER_PARAM_BF16) {  // this DP rank's slice of the fp32 buffers
-                        base = dp * st.S;
-                        lo = std::max(lo, base);
-                        hi = std::min(hi, base + st.S);
-                    }
-                    if (lo >= hi) continue;
+        for (const ZeroRegion& z : col.zeros) {  // vocabulary padding rows and the padding of every bucket
+            if (kind_on(LIVER_PARAM_BF16))
+                for (int dp = 0; dp < D.dp; ++dp) {
+                    if (!dst_dp_planned(dp)) continue;
                     Entry e;
                     e.slot = z.slot;
-                    e.run = hi - lo;
-                    e.dsts.push_back({rank, k, LIVER_OP_ZERO, lo - base, hi - lo});
+                    e.run = z.n;
+                    e.dsts.push_back({rank_of(D, col.tp, col.pp, dp), LIVER_PARAM_BF16, LIVER_OP_ZERO, z.off, z.n});
+                    push_bounded(std::move(e));
+                }
+            // fp32 kinds: the region may span several DP ranks' slices
+            std::vector<i64> cuts{z.off, z.off + z.n};
+            for (auto it = std::upper_bound(st.bounds.begin(), st.bounds.end(), z.off); it != st.bounds.end() && *it < z.off + z.n; ++it)
+                cuts.push_back(*it);
+            std::sort(cuts.begin(), cuts.end());
+            for (size_t c = 0; c + 1 < cuts.size(); ++c) {
+                int dp;
+                i64 local;
+                locate(st, cuts[c], dp, local);
+                if (!dst_dp_planned(dp)) continue;
+                for (int k = LIVER_MASTER_F32; k <= LIVER_ADAM_V_F32; ++k) {
+                    if (!kind_on(k)) continue;
+                    Entry e;
+                    e.slot = z.slot;
+                    e.run = cuts[c + 1] - cuts[c];
+                    e.dsts.push_back({rank_of(D, col.tp, col.pp, dp), k, LIVER_OP_ZERO, local, e.run});
                     push_bounded(std::move(e));
                 }
             }
+        }
     }
 
     int run();
@@ -355,8 +399,8 @@ int Builder::run() {
     }
     for (const liver_layout_t* l : {&S, &D})
         if (l->tp <= 0 || l->pp <= 0 || l->dp <= 0 || l->pad_multiple <= 0 || l->vpp < 0 || l->vocab_multiple < 0 ||
-            l->pp_first < 0 || l->pp_last < 0) {
-            why = "layout: tp, pp, dp, pad_multiple must be positive, vpp, vocab_multiple, pp_first, pp_last non-negative";
+            l->pp_first < 0 || l->pp_last < 0 || l->bucket_elems < 0) {
+            why = "layout: tp, pp, dp, pad_multiple must be positive; vpp, vocab_multiple, pp_first, pp_last, bucket_elems non-negative";
             return LIVER_E_INVALID_ARG;
         }
     if (plan.chunk_bytes < 256 || plan.chunk_bytes % 256) {
@@ -399,12 +443,18 @@ int Builder::run() {
     // --- views of both worlds (Abstract Resource View) ---------------------------------
     auto stage_sizes = [&](const liver_layout_t& lay, std::vector<StageSize>& out) {
         out.resize(lay.pp);
-        const i64 quantum = (i64)lay.dp * lay.pad_multiple;
         for (int pp = 0; pp < lay.pp; ++pp) {
+            const Column c = build_column(g, lay, 0, pp);
             StageSize s;
-            s.n_local = build_column(g, lay, 0, pp).n_local;
-            s.n_pad = (s.n_local + quantum - 1) / quantum * quantum;
-            s.S = s.n_pad / lay.dp;
+            s.n_local = c.n_local, s.n_pad = c.n_pad, s.S = c.n_pad / lay.dp;
+            i64 prefix = 0;
+            for (const auto& b : c.buckets) {
+                Bucket k;
+                k.start = b.first, k.padded = b.second, k.slice = b.second / lay.dp, k.prefix = prefix;
+                prefix += k.slice;
+                for (int d = 0; d < lay.dp; ++d) s.bounds.push_back(k.start + d * k.slice);
+                s.buckets.push_back(k);
+            }
             out[pp] = s;
         }
     };

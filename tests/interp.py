@@ -18,9 +18,9 @@ def lv_objects(cfg_or_spec, src, dst, **dst_kw):
     spec = lv.ModelSpec(s.n_layers, s.hidden, s.n_q_heads, s.n_kv_heads, s.ffn, s.vocab, s.max_pos, s.glu,
                         s.norm_bias, s.linear_bias, s.tied_embed)
     a = lv.Layout(src.tp, src.pp, src.dp, src.pad_multiple, vpp=src.vpp, vocab_multiple=src.vocab_multiple, pp_first=src.pp_first,
-                  pp_last=src.pp_last)
+                  pp_last=src.pp_last, bucket_elems=src.bucket_elems)
     b = lv.Layout(dst.tp, dst.pp, dst.dp, dst.pad_multiple, vpp=dst.vpp, vocab_multiple=dst.vocab_multiple, pp_first=dst.pp_first,
-                  pp_last=dst.pp_last, **dst_kw)
+                  pp_last=dst.pp_last, bucket_elems=dst.bucket_elems, **dst_kw)
     return spec, a, b
 
 

@@ -61,8 +61,11 @@ def uneven_stage_range(L, PP, pp, first, last):
     return lo, lo + count(pp)
 
 
-def stage_param_sizes(spec, TP, PP, pp, vpp=1, vm=0, first=0, last=0):
+def stage_param_sizes(spec, lay, pp):
+    """[(physical name, element count)] of stage pp on one TP rank, in flat-buffer order.
+    `lay` is any object with tp, pp, dp, pad_multiple, vpp, vocab_multiple, pp_first, pp_last, bucket_elems."""
     H, hd, Q, KV, F, V = dims(spec)
+    TP, PP, vpp, vm, first, last = lay.tp, lay.pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last
     out = []
     if pp == 0:
         out.append(("embed.word", vocab_rows(spec, TP, vm) * H))
@@ -88,19 +91,54 @@ def stage_param_sizes(spec, TP, PP, pp, vpp=1, vm=0, first=0, last=0):
     return out
 
 
-def n_local(spec, TP, PP, pp, vpp=1, vm=0, first=0, last=0):
-    return sum(n for _, n in stage_param_sizes(spec, TP, PP, pp, vpp, vm, first, last))
+def bucket_table(spec, lay, pp):
+    """[(start, used, padded)] of the buckets of stage pp's flat buffer.  Parameters are appended in order; a
+    bucket closes after the parameter that brings it to >= bucket_elems elements (bucket_elems 0: one bucket);
+    every bucket is zero-padded to a multiple of DP*pad_multiple elements."""
+    sizes = stage_param_sizes(spec, lay, pp)
+    q = lay.dp * lay.pad_multiple
+    out, start, used = [], 0, 0
+    for i, (_, n) in enumerate(sizes):
+        used += n
+        if (lay.bucket_elems and used >= lay.bucket_elems) or i == len(sizes) - 1:
+            padded = (used + q - 1) // q * q
+            out.append((start, used, padded))
+            start, used = start + padded, 0
+    return out
 
 
-def n_pad(spec, TP, PP, DP, pad_multiple, pp, vpp=1, vm=0, first=0, last=0):
-    q = DP * pad_multiple
-    return (n_local(spec, TP, PP, pp, vpp, vm, first, last) + q - 1) // q * q
+def n_local(spec, lay, pp):
+    """End of the last parameter in the flat buffer (interior bucket padding included)."""
+    start, used, _ = bucket_table(spec, lay, pp)[-1]
+    return start + used
 
 
-def owner(spec, TP, tp, phys, k, vm=0):
+def n_pad(spec, lay, pp):
+    start, _, padded = bucket_table(spec, lay, pp)[-1]
+    return start + padded
+
+
+def shard_location(spec, lay, pp):
+    """(dp_of, local_of): for every flat position 0..N_pad-1 of the fp32 buffers, the DP rank that holds it and
+    its offset in that rank's buffer.  Each bucket is cut into DP equal slices; a rank's buffer is the
+    concatenation of its slice of every bucket."""
+    npad = n_pad(spec, lay, pp)
+    dp_of, local_of = np.zeros(npad, np.int64), np.zeros(npad, np.int64)
+    prefix = 0
+    for start, _, padded in bucket_table(spec, lay, pp):
+        Sb = padded // lay.dp
+        k = np.arange(padded, dtype=np.int64)
+        dp_of[start:start + padded] = k // Sb
+        local_of[start:start + padded] = prefix + k % Sb
+        prefix += Sb
+    return dp_of, local_of
+
+
+def owner(spec, lay, tp, phys, k):
     """(names, idx): logical tensor name and row-major logical index of local
     elements k (int64 array) of physical parameter `phys` on TP rank `tp`."""
     H, hd, Q, KV, F, V = dims(spec)
+    TP, vm = lay.tp, lay.vocab_multiple
     k = np.asarray(k, np.int64)
     base = phys.split("(")[0]
     pre = base[:base.index(".") + 1] if base.startswith("L") else ""
@@ -165,22 +203,31 @@ def owner(spec, TP, tp, phys, k, vm=0):
     raise KeyError(phys)
 
 
-def column_ownership(spec, TP, PP, tp, pp, vpp=1, vm=0, first=0, last=0):
-    """For flat offsets 0..N_local-1 of rank column (tp, pp): (names, idx, canonical).
-    names[k] is None where the element is vocabulary padding.
+def column_ownership(spec, lay, tp, pp):
+    """For flat positions 0..N_pad-1 of rank column (tp, pp): (names, idx, canonical).
 
-    canonical[k] is False where the element is a replica that a gather must not
-    read: TP-replicated parameters on tp > 0 and the tied-embedding copy."""
-    names, idx, canon = [], [], []
-    for phys, n in stage_param_sizes(spec, TP, PP, pp, vpp, vm, first, last):
-        nm, ix = owner(spec, TP, tp, phys, np.arange(n, dtype=np.int64), vm)
-        names.append(nm)
-        idx.append(ix)
+    names[k] is None where the position holds padding (bucket padding, tail padding, vocabulary padding rows).
+    canonical[k] is False where the element is a replica that a gather must not read: TP-replicated
+    parameters on tp > 0, replicated k / v heads on all but the first rank of their group, and the
+    tied-embedding copy."""
+    TP = lay.tp
+    npad = n_pad(spec, lay, pp)
+    names = np.full(npad, None, dtype=object)
+    idx = np.zeros(npad, np.int64)
+    canon = np.zeros(npad, bool)
+    sizes = stage_param_sizes(spec, lay, pp)
+    q = lay.dp * lay.pad_multiple
+    pos, used = 0, 0
+    for phys, n in sizes:
+        nm, ix = owner(spec, lay, tp, phys, np.arange(n, dtype=np.int64))
         leaf = phys.split(".", 1)[1] if phys.startswith("L") else phys
         replicated = leaf in ("ln1.w", "ln1.b", "ln2.w", "ln2.b", "o.b", "down.b", "final_norm.w",
                               "final_norm.b", "embed.pos")
         ok = np.full(n, not (replicated and tp > 0) and "(tied copy)" not in phys)
         if leaf in ("qkv.w", "qkv.b") and spec.n_kv_heads % TP and tp % (TP // spec.n_kv_heads):
             ok &= np.char.endswith(nm.astype(str), ("q." + leaf[-1]))      # replicated k / v: read from part 0 only
-        canon.append(ok)
-    return np.concatenate(names), np.concatenate(idx), np.concatenate(canon)
+        names[pos:pos + n], idx[pos:pos + n], canon[pos:pos + n] = nm, ix, ok
+        pos, used = pos + n, used + n
+        if lay.bucket_elems and used >= lay.bucket_elems:                  # bucket closes: skip its padding
+            pos, used = pos + (-used) % q, 0
+    return names, idx, canon

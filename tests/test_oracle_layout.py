@@ -31,7 +31,8 @@ LAYOUTS = [(1, 1, 1, 128), (2, 1, 2, 128), (1, 2, 2, 128), (2, 2, 3, 4), (4, 2, 
            (2, 2, 2, 4, 2), (1, 1, 1, 1, 2), (1, 2, 3, 1, 1),       # 5th entry: vpp (interleaved stages)
            (8, 1, 2, 4),                                            # TP 8 > n_kv: replicated kv heads
            (2, 2, 2, 4, 1, 8), (4, 1, 1, 1, 1, 4), (1, 1, 2, 1, 1, 16), (4, 2, 3, 128, 1, 32),   # 6th: vocab_multiple
-           (1, 2, 2, 4, 1, 0, 1, 0), (2, 2, 1, 1, 1, 0, 3, 1), (1, 3, 1, 1, 1, 0, 1, 1)]         # 7th, 8th: pp_first, pp_last
+           (1, 2, 2, 4, 1, 0, 1, 0), (2, 2, 1, 1, 1, 0, 3, 1), (1, 3, 1, 1, 1, 0, 1, 1),         # 7th, 8th: pp_first, pp_last
+           (2, 1, 3, 4, 1, 0, 0, 0, 3000), (1, 2, 2, 128, 1, 0, 0, 0, 1), (2, 2, 2, 1, 2, 8, 0, 0, 5000)]   # 9th: bucket_elems
 
 
 def _cases():
@@ -42,7 +43,7 @@ def _cases():
                 oracle.check_supported(spec, lay)
             except ValueError:
                 continue
-            yield pytest.param(spec, lay, id=f"{sname}-tp{tp}pp{pp}dp{dp}pm{pm}v{lay.vpp}vm{lay.vocab_multiple}")
+            yield pytest.param(spec, lay, id=f"{sname}-tp{tp}pp{pp}dp{dp}pm{pm}v{lay.vpp}vm{lay.vocab_multiple}f{lay.pp_first}l{lay.pp_last}b{lay.bucket_elems}")
 
 
 def _tensor_ordinal_state(spec):
@@ -62,24 +63,23 @@ def test_split_matches_ownership(spec, lay):
     w_hi = make_world(spec, lay, synth.index_encoded_state(shapes, half=1), poison=False)
     w_ord = make_world(spec, lay, _tensor_ordinal_state(spec), poison=False)
     for pp in range(lay.pp):
-        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last)
-        S = npad // lay.dp
+        npad = own.n_pad(spec, lay, pp)
+        dp_of, local_of = own.shard_location(spec, lay, pp)
         for tp in range(lay.tp):
-            names, idx, _ = own.column_ownership(spec, lay.tp, lay.pp, tp, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last)
-            nl = len(names)
-            exp_idx = np.zeros(npad, np.int64)
-            exp_idx[:nl] = idx
-            exp_ord = np.zeros(npad, np.int64)
-            exp_ord[:nl] = [ordinal.get(n, 0) for n in names]       # vocabulary padding owns nothing: 0
+            names, idx, _ = own.column_ownership(spec, lay, tp, pp)       # padding: name None, index 0
+            exp_idx = idx
+            exp_ord = np.array([ordinal.get(n, 0) for n in names], np.int64)
             for dp in range(lay.dp):
                 r = lay.rank(tp, pp, dp)
                 assert np.array_equal(w_idx[(r, oracle.PARAM)], (exp_idx & 0xFFFF).astype(np.uint16))
                 assert np.array_equal(w_hi[(r, oracle.PARAM)], ((exp_idx >> 16) & 0xFFFF).astype(np.uint16))
                 assert np.array_equal(w_ord[(r, oracle.PARAM)], exp_ord.astype(np.uint16))
+                mine = np.flatnonzero(dp_of == dp)
+                assert np.array_equal(local_of[mine], np.arange(npad // lay.dp))      # a rank's buffer is dense
                 for k in (oracle.MASTER, oracle.ADAM_M, oracle.ADAM_V):
-                    assert w_idx[(r, k)].shape == (S,)
-                    assert np.array_equal(w_idx[(r, k)], exp_idx[dp * S:(dp + 1) * S].astype(np.uint32))
-                    assert np.array_equal(w_ord[(r, k)], exp_ord[dp * S:(dp + 1) * S].astype(np.uint32))
+                    assert w_idx[(r, k)].shape == (npad // lay.dp,)
+                    assert np.array_equal(w_idx[(r, k)], exp_idx[mine].astype(np.uint32))
+                    assert np.array_equal(w_ord[(r, k)], exp_ord[mine].astype(np.uint32))
 
 
 @pytest.mark.parametrize("spec,lay", list(_cases()))
@@ -175,3 +175,23 @@ def test_uneven_stage_layers():
         for p in range(lay.pp):
             assert own.uneven_stage_range(10, lay.pp, p, lay.pp_first, lay.pp_last) == \
                 (oracle.stage_layers(spec, lay, p)[0], oracle.stage_layers(spec, lay, p)[-1] + 1)
+
+
+def test_bucket_boundaries_closed_form():
+    """bucket_elems = 300 on a 1-layer toy model: parameters fill buckets in order, a bucket closes after the
+    parameter that reaches 300 elements, every bucket is padded to DP*pad_multiple = 8."""
+    spec = oracle.ModelSpec(n_layers=1, hidden=8, n_q_heads=2, n_kv_heads=2, ffn=16, vocab=20)
+    lay = oracle.Layout(1, 1, 2, 4, bucket_elems=300)
+    sv = oracle.stage_view(spec, lay, 0, 0)
+    sizes = [(p.name, p.size) for p in sv.params]
+    assert sizes == [("embed.word", 160), ("L0.ln1.w", 8), ("L0.qkv.w", 192), ("L0.o.w", 64), ("L0.ln2.w", 8),
+                     ("L0.fc1.w", 128), ("L0.fc2.w", 128), ("final_norm.w", 8), ("lm_head.w", 160)]
+    # bucket 0: 160+8+192 = 360 -> padded 360; bucket 1: 64+8+128+128 = 328 -> padded 328; bucket 2: 8+160 = 168 -> 168
+    assert sv.buckets == [(0, 360), (360, 328), (688, 168)] and sv.n_pad == 856 and sv.S == 428
+    assert [p.offset for p in sv.params] == [0, 160, 168, 360, 424, 432, 560, 688, 696]
+    lay3 = oracle.Layout(1, 1, 3, 4, bucket_elems=300)            # quantum 12: 360, 336 (328 + 8 pad), 168
+    sv3 = oracle.stage_view(spec, lay3, 0, 0)
+    assert sv3.buckets == [(0, 360), (360, 336), (696, 168)] and sv3.n_local == 864 - 0 and sv3.n_pad == 864
+    # DP rank 1 of 3 holds the middle third of every bucket, concatenated
+    assert oracle.dp_pieces(sv3, lay3, 0, 864)[1::3] == [(1, 0, 120, 120), (1, 120, 472, 112), (1, 232, 752, 56)]
+    assert own.bucket_table(spec, lay3, 0) == [(0, 360, 360), (360, 328, 336), (696, 168, 168)]

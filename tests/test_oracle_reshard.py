@@ -44,6 +44,10 @@ BRUTE = [
     (VOCH, (1, 1, 1, 1, 1, 64), (4, 2, 1, 1, 1, 16)),   # tp 3 holds rows 48..63: all padding (and kv heads replicated)
     (ODD6, (2, 3, 1, 4), (1, 3, 2, 1, 1, 0, 1, 3)),     # even stages -> 1 / 2 / 3 layers (7th, 8th = pp_first, pp_last)
     (ODD6, (3, 2, 2, 1, 1, 0, 5, 0), (2, 4, 1, 4, 1, 0, 0, 3)),   # 5 / 1 -> 1 / 1 / 1 / 3
+    (ODD, (2, 1, 2, 4, 1, 0, 0, 0, 700), (1, 2, 3, 4, 1, 0, 0, 0, 0)),        # bucketed (9th = bucket_elems) -> one bucket
+    (ODD, (1, 2, 3, 1), (2, 2, 2, 4, 1, 0, 0, 0, 500)),                       # one bucket -> bucketed, padding inside
+    (ODD6, (3, 2, 3, 4, 1, 0, 0, 0, 900), (2, 3, 2, 8, 1, 0, 0, 0, 400)),     # buckets on both sides, different cuts
+    (VOC, (2, 1, 2, 4, 1, 8, 0, 0, 300), (1, 2, 3, 4, 1, 4, 0, 0, 1)),        # with vocabulary padding; one bucket per parameter
 ]
 
 
@@ -126,7 +130,7 @@ def test_dp_only_replicated_params(dp_src, dp_dst):
     world = make_world(spec, src, synth.logical_state(oracle.logical_tensors(spec), 2, "normal"), poison=False)
     out = oracle.reshard_state(spec, src, dst, world)
     for tp in range(2):
-        nl = own.n_local(spec, 2, 1, 0)
+        nl = own.n_local(spec, src, 0)
         ref = world[(src.rank(tp, 0, 0), oracle.PARAM)][:nl]
         for dp in range(dp_dst):
             assert np.array_equal(out[(dst.rank(tp, 0, dp), oracle.PARAM)][:nl], ref)
@@ -180,7 +184,7 @@ def test_target_equals_static_split_and_pads_are_zero(tiny_world):
         out = oracle.reshard_state(spec, A, B, make_world(spec, A, state))
         assert_same(out, make_world(spec, B, state, poison=False), "static reference")
         for pp in range(B.pp):
-            nl = own.n_local(spec, B.tp, B.pp, pp)
+            nl = own.n_local(spec, B, pp)
             for tp in range(B.tp):
                 for dp in range(B.dp):
                     assert not out[(B.rank(tp, pp, dp), oracle.PARAM)][nl:].any()

@@ -39,7 +39,7 @@ def test_n_local_closed_form(key):
     for tp in {0, lay.tp - 1}:
         sv = oracle.stage_view(spec, lay, tp, pp)
         assert sv.n_local == SIZES[key]
-        assert sv.n_local == own.n_local(spec, lay.tp, lay.pp, pp)
+        assert sv.n_local == own.n_local(spec, lay, pp) and sv.n_pad == own.n_pad(spec, lay, pp)
         assert sv.n_local == sum(p.size for p in sv.params)
         offs = [p.offset for p in sv.params]
         assert offs == sorted(offs) and offs[0] == 0

@@ -16,22 +16,32 @@ def cfg_objects(name):
     return cfg, spec, src, dst
 
 
+def _scatter(spec, lay, bufs, tp, pp, positions, fn16, fn32):
+    """Apply fn16 / fn32 (in place, on index arrays) to the given flat positions of rank column (tp, pp) in
+    every buffer that holds them: all PARAM replicas, and the owning DP rank's fp32 buffers."""
+    dp_of, local_of = own.shard_location(spec, lay, pp)
+    for dp in range(lay.dp):
+        r = lay.rank(tp, pp, dp)
+        if (r, oracle.PARAM) in bufs:
+            fn16(bufs[(r, oracle.PARAM)], positions, dp)
+        mine = local_of[positions[dp_of[positions] == dp]]
+        for k in (oracle.MASTER, oracle.ADAM_M, oracle.ADAM_V):
+            if (r, k) in bufs:
+                fn32(bufs[(r, k)], mine)
+
+
 def poison_pads(spec, lay, bufs):
-    """Overwrite the padding of every buffer of world `lay` with NaN sentinels
-    (source padding must never be read by a reshard)."""
+    """Overwrite every padding element of world `lay` (bucket padding, tail padding, vocabulary padding rows)
+    with NaN sentinels: source padding must never be read by a reshard."""
+    def f16(a, pos, dp):
+        a[pos] = NAN16
+
+    def f32(a, pos):
+        a[pos] = NAN32
     for pp in range(lay.pp):
-        nl = own.n_local(spec, lay.tp, lay.pp, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last)
-        npad = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last)
-        S = npad // lay.dp
         for tp in range(lay.tp):
-            for dp in range(lay.dp):
-                r = lay.rank(tp, pp, dp)
-                if (r, oracle.PARAM) in bufs:
-                    bufs[(r, oracle.PARAM)][nl:npad] = NAN16
-                lo = max(nl - dp * S, 0)
-                for k in (oracle.MASTER, oracle.ADAM_M, oracle.ADAM_V):
-                    if (r, k) in bufs and lo < S:
-                        bufs[(r, k)][lo:S] = NAN32
+            names, _, _ = own.column_ownership(spec, lay, tp, pp)
+            _scatter(spec, lay, bufs, tp, pp, np.flatnonzero(np.equal(names, None)), f16, f32)
     return bufs
 
 
@@ -44,24 +54,21 @@ def make_world(spec, lay, state, poison=True, kinds=oracle.KINDS):
 
 
 def corrupt_replicas(spec, lay, bufs):
-    """Flip bits in every copy a gather must NOT read, located by the ownership
-    formulas (not by the oracle): TP-replicated parameters on tp > 0, the tied
-    embedding copy, PARAM replicas with dp > 0, and vocabulary padding rows."""
+    """Flip bits in every copy a gather must NOT read, located by the ownership formulas (not by the oracle):
+    TP-replicated parameters on tp > 0, replicated k / v heads, the tied embedding copy, all padding, and the
+    whole PARAM buffer of the replicas with dp > 0."""
+    def f16(a, pos, dp):
+        if dp > 0:
+            a ^= 0x00FF
+        else:
+            a[pos] ^= 0x5555
+
+    def f32(a, pos):
+        a[pos] ^= 0x55555555
     for pp in range(lay.pp):
-        nl = own.n_local(spec, lay.tp, lay.pp, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last)
-        S = own.n_pad(spec, lay.tp, lay.pp, lay.dp, lay.pad_multiple, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last) // lay.dp
         for tp in range(lay.tp):
-            names, _, canon = own.column_ownership(spec, lay.tp, lay.pp, tp, pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last)
-            bad = np.flatnonzero(~canon | np.equal(names, None))       # copies, and vocabulary padding
-            for dp in range(lay.dp):
-                r = lay.rank(tp, pp, dp)
-                if dp > 0:
-                    bufs[(r, oracle.PARAM)][:nl] ^= 0x00FF
-                else:
-                    bufs[(r, oracle.PARAM)][bad] ^= 0x5555
-                mine = bad[(bad >= dp * S) & (bad < (dp + 1) * S)] - dp * S
-                for k in (oracle.MASTER, oracle.ADAM_M, oracle.ADAM_V):
-                    bufs[(r, k)][mine] ^= 0x55555555
+            names, _, canon = own.column_ownership(spec, lay, tp, pp)
+            _scatter(spec, lay, bufs, tp, pp, np.flatnonzero(~canon | np.equal(names, None)), f16, f32)
     return bufs
 
 
@@ -81,39 +88,38 @@ def brute_reshard(spec, src, dst, src_bufs, derive=False):
     alone (tiny models only).  Independent of the oracle's slicing."""
     value = {k: {} for k in oracle.KINDS}
     for pp in range(src.pp):
-        npad = own.n_pad(spec, src.tp, src.pp, src.dp, src.pad_multiple, pp, src.vpp, src.vocab_multiple, src.pp_first, src.pp_last)
-        S = npad // src.dp
+        dp_of, local_of = own.shard_location(spec, src, pp)
         for tp in range(src.tp):
-            names, idx, canon = own.column_ownership(spec, src.tp, src.pp, tp, pp, src.vpp, src.vocab_multiple, src.pp_first, src.pp_last)
+            names, idx, canon = own.column_ownership(spec, src, tp, pp)
             for k in range(len(names)):
                 if not canon[k] or names[k] is None:
                     continue
                 key = (names[k], int(idx[k]))
                 assert key not in value[oracle.PARAM], ("owned twice", key)
                 value[oracle.PARAM][key] = src_bufs[(src.rank(tp, pp, 0), oracle.PARAM)][k]
-                d = k // S
                 for kind in (oracle.MASTER, oracle.ADAM_M, oracle.ADAM_V):
-                    value[kind][key] = src_bufs[(src.rank(tp, pp, d), kind)][k - d * S]
+                    value[kind][key] = src_bufs[(src.rank(tp, pp, int(dp_of[k])), kind)][local_of[k]]
     if derive:
         value[oracle.PARAM] = {key: _rne_scalar(int(v)) for key, v in value[oracle.MASTER].items()}
     out = {}
     for pp in range(dst.pp):
-        npad = own.n_pad(spec, dst.tp, dst.pp, dst.dp, dst.pad_multiple, pp, dst.vpp, dst.vocab_multiple, dst.pp_first, dst.pp_last)
-        S = npad // dst.dp
+        npad = own.n_pad(spec, dst, pp)
+        dp_of, local_of = own.shard_location(spec, dst, pp)
         for tp in range(dst.tp):
-            names, idx, _ = own.column_ownership(spec, dst.tp, dst.pp, tp, pp, dst.vpp, dst.vocab_multiple, dst.pp_first, dst.pp_last)
-            flat = {kind: np.zeros(npad, oracle.WORD[kind]) for kind in oracle.KINDS}
-            for k in range(len(names)):
-                if names[k] is None:            # vocabulary padding stays +0
-                    continue
-                key = (names[k], int(idx[k]))
-                for kind in oracle.KINDS:
-                    flat[kind][k] = value[kind][key]
+            names, idx, _ = own.column_ownership(spec, dst, tp, pp)
             for dp in range(dst.dp):
                 r = dst.rank(tp, pp, dp)
-                out[(r, oracle.PARAM)] = flat[oracle.PARAM].copy()
+                out[(r, oracle.PARAM)] = np.zeros(npad, np.uint16)
                 for kind in (oracle.MASTER, oracle.ADAM_M, oracle.ADAM_V):
-                    out[(r, kind)] = flat[kind][dp * S:(dp + 1) * S].copy()
+                    out[(r, kind)] = np.zeros(npad // dst.dp, np.uint32)
+            for k in range(len(names)):
+                if names[k] is None:            # padding stays +0
+                    continue
+                key = (names[k], int(idx[k]))
+                for dp in range(dst.dp):
+                    out[(dst.rank(tp, pp, dp), oracle.PARAM)][k] = value[oracle.PARAM][key]
+                for kind in (oracle.MASTER, oracle.ADAM_M, oracle.ADAM_V):
+                    out[(dst.rank(tp, pp, int(dp_of[k])), kind)][local_of[k]] = value[kind][key]
     return out
 
 
