@@ -131,3 +131,25 @@ def fill_device_world(sizes: dict, dp: int, seed: int, device: str = "cuda"):
                 out[(c, d, kind)] = t
         out[(c, "param")] = torch.cat([out[(c, d, MASTER)].to(torch.bfloat16) for d in range(dp)])
     return out
+
+
+def fill_device_world_into(columns: dict, seed: int) -> None:
+    """Same values as fill_device_world, written into buffers the caller has already allocated.
+
+    columns: {column key: {"master": [tensor per DP slice], "m": [...], "v": [...], "param": bf16 tensor or None}}
+    (fp32 tensors; param holds the bf16 of the concatenated MASTER slices)."""
+    import torch
+    for ci, c in enumerate(sorted(columns)):
+        col = columns[c]
+        device = col["master"][0].device
+        g = torch.Generator(device=device)
+        pos = 0
+        for d, master in enumerate(col["master"]):
+            for kind, t in ((MASTER, master), (ADAM_M, col["m"][d]), (ADAM_V, col["v"][d])):
+                g.manual_seed(((seed * 1000003 + ci) * 64 + d) * 4 + kind)
+                t.normal_(0.0, 0.02, generator=g)
+                if kind == ADAM_V:
+                    t.abs_()
+            if col.get("param") is not None:
+                col["param"][pos:pos + master.numel()].copy_(master)       # fp32 -> bf16 (round to nearest even)
+            pos += master.numel()

@@ -53,6 +53,19 @@ int run_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uin
         const bool auto_interleave = &list == &plan->direct && pass.n_tiles < (48u << 14);  // < 48 GiB of 64 KiB tiles
         args.tile_order = plan->tile_order >= 0 ? (uint32_t)plan->tile_order : (auto_interleave ? 1u : 0u);
         args.reserved = 0;
+        // scattered order: groups of up to 64 tiles (4 MiB), at least ~32 groups per workgroup; the groups
+        // are visited in a multiplicative permutation with a multiplier near 0.618 * n_groups
+        {
+            const uint32_t g_max = plan->grid_blocks > 0 ? (uint32_t)plan->grid_blocks : (uint32_t)plan->n_cu;
+            uint32_t group = pass.n_tiles / (g_max * 32u);
+            group = group < 1 ? 1 : group > 64 ? 64 : group;
+            const uint32_t n_groups = (pass.n_tiles + group - 1) / group;
+            uint32_t mul = (uint32_t)(0.6180339887 * n_groups) | 1u;
+            auto gcd = [](uint32_t a, uint32_t b) { while (b) { const uint32_t t = a % b; a = b; b = t; } return a; };
+            while (mul > 1 && gcd(mul, n_groups) != 1) mul -= 2;
+            if (mul < 1 || n_groups < 3) mul = 1;
+            args.group = group, args.perm_mul = mul;
+        }
         size_t i = 0;
         for (const liver::BufRef& r : pass.bufs) {
             const void* ptr = r.side == 0 ? src_bufs[(size_t)r.rank * 4 + r.kind]
@@ -159,7 +172,7 @@ int liver_plan_desc(const liver_plan_t* plan, int list, int64_t i, liver_desc_t*
 }
 
 int liver_plan_set_launch(liver_plan_t* plan, int grid_blocks, int tile_order, int cache_hints) {
-    if (!plan || grid_blocks < 0 || grid_blocks > 65536 || tile_order < -1 || tile_order > 1 || cache_hints < -1 ||
+    if (!plan || grid_blocks < 0 || grid_blocks > 65536 || tile_order < -1 || tile_order > 2 || cache_hints < -1 ||
         cache_hints > 3)
         return fail(LIVER_E_INVALID_ARG, "bad launch shape");
     plan->grid_blocks = grid_blocks, plan->tile_order = tile_order, plan->cache_hints = cache_hints;

@@ -144,22 +144,11 @@ __device__ __forceinline__ void tile_zero(uint32_t u0, uint32_t n, char* b) {
     for (uint32_t i = threadIdx.x; i < n; i += BLOCK) *(T*)(b + ((uint64_t)(u0 + i)) * sizeof(T)) = z;
 }
 
-template <bool NTL, bool NTS>
-__global__ __launch_bounds__(BLOCK) void liver_copy_kernel(const PassArgs args) {
-    typedef Mem<NTL, NTS> M;
-    const uint32_t n_tiles = args.n_tiles, G = gridDim.x, w = blockIdx.x;
-    uint32_t t, t_end, step;
-    if (args.tile_order == 0) {  // one contiguous range of tiles per workgroup
-        const uint32_t per = (n_tiles + G - 1) / G;
-        t = w * per;             // w * per <= n_tiles + G: no overflow, both below 2^32 by the host's check
-        t_end = t + per < n_tiles ? t + per : n_tiles;
-        step = 1;
-    } else {                     // workgroups interleave tile by tile
-        t = w;
-        t_end = n_tiles;
-        step = G;
-    }
-    if (t >= t_end) return;
+// Everything one workgroup does for tiles [t, t_end) with stride `step`: find the descriptor of the
+// first tile (binary search), then walk forward through the descriptor table.
+template <class M>
+__device__ __forceinline__ void run_tiles(const PassArgs& args, uint32_t t, uint32_t t_end, uint32_t step) {
+    const uint32_t n_tiles = args.n_tiles;
     const DevDesc* __restrict__ descs = args.descs;
     // last descriptor whose first tile is <= t  (descs[0].tile_begin == 0)
     uint32_t lo = 0, hi = args.n_desc;
@@ -194,6 +183,27 @@ __global__ __launch_bounds__(BLOCK) void liver_copy_kernel(const PassArgs args) 
             case DOP_ZERO_E2: tile_zero<uint16_t>(u0, n, b); break;
             case DOP_ZERO_E4: tile_zero<uint32_t>(u0, n, b); break;
             default: break;
+        }
+    }
+}
+
+template <bool NTL, bool NTS>
+__global__ __launch_bounds__(BLOCK) void liver_copy_kernel(const PassArgs args) {
+    typedef Mem<NTL, NTS> M;
+    const uint32_t n_tiles = args.n_tiles, G = gridDim.x, w = blockIdx.x;
+    if (args.tile_order == 0) {         // one contiguous range of tiles per workgroup
+        const uint32_t per = (n_tiles + G - 1) / G;
+        const uint32_t t = w * per;     // below 2^32: n_tiles < 2^31 and G <= n_tiles (host checks)
+        if (t < n_tiles) run_tiles<M>(args, t, t + per < n_tiles ? t + per : n_tiles, 1);
+    } else if (args.tile_order == 1) {  // workgroups interleave tile by tile
+        if (w < n_tiles) run_tiles<M>(args, w, n_tiles, G);
+    } else {                            // scattered: groups of `group` consecutive tiles, visited in the order
+                                        // i -> (i * perm_mul) mod n_groups (perm_mul coprime to n_groups)
+        const uint32_t group = args.group, n_groups = (n_tiles + group - 1) / group;
+        for (uint32_t i = w; i < n_groups; i += G) {
+            const uint32_t gi = (uint32_t)(((uint64_t)i * args.perm_mul) % n_groups);
+            const uint32_t t = gi * group;
+            run_tiles<M>(args, t, t + group < n_tiles ? t + group : n_tiles, 1);
         }
     }
 }

@@ -12,7 +12,9 @@ struct PassArgs {
     const DevDesc* descs;
     uint32_t n_desc;
     uint32_t n_tiles;
-    uint32_t tile_order;
+    uint32_t tile_order;  // 0 contiguous ranges, 1 interleaved tiles, 2 scattered groups
+    uint32_t group;       // tile_order 2: tiles per group (>= 1)
+    uint32_t perm_mul;    // tile_order 2: multiplier of the group permutation, coprime to the group count
     uint32_t reserved;
     char* bufs[MAX_PASS_BUFS];
 };

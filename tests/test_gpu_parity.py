@@ -132,7 +132,8 @@ def test_gpt2_small_derive(gpt2):
     check_against(run_staged(plan, dev), want, plan, "derive staged")
 
 
-@pytest.mark.parametrize("grid,order,hints", [(1, 0, 0), (7, 1, 3), (256, 0, 1), (2048, 1, 2), (65536, 0, 3), (0, 1, 0)])
+@pytest.mark.parametrize("grid,order,hints", [(1, 0, 0), (7, 1, 3), (256, 0, 1), (2048, 1, 2), (65536, 0, 3), (0, 1, 0),
+                                              (256, 2, 3), (0, 2, -1), (5, 2, 0), (4096, 2, -1)])
 def test_gpt2_small_launch_shapes(gpt2, grid, order, hints):
     """The result does not depend on grid size, tile order or cache hints."""
     cfg, spec, src, dst, world, want, dev = gpt2
@@ -202,3 +203,16 @@ def test_round_trip_on_device():
     there, back = _plan(spec, src, dst, 1 << 20), _plan(spec, dst, src, 1 << 20)
     mid = run_direct(there, to_dev(world))
     check_against(run_direct(back, mid), world, back, "A->B->A")
+
+
+def test_many_buffers_split_into_passes():
+    """More buffers than one launch's argument table holds: the direct list runs as several launches."""
+    print("many buffers", flush=True)
+    spec = oracle.ModelSpec(n_layers=8, hidden=64, n_q_heads=8, n_kv_heads=8, ffn=64, vocab=64, tied_embed=True)
+    src, dst = oracle.Layout(8, 8, 8, 8), oracle.Layout(4, 4, 8, 8)
+    world = make_world(spec, src, synth.logical_state(oracle.logical_tensors(spec), 11, "uniform"))
+    want = oracle.reshard_state(spec, src, dst, world)
+    plan = _plan(spec, src, dst, 1 << 16)
+    dev = to_dev(world)
+    check_against(run_direct(plan, dev), want, plan, "direct, multi-pass")
+    check_against(run_staged(plan, dev), want, plan, "staged")

@@ -270,3 +270,13 @@ def test_pieces_above_2_30_elements_are_split():
                 assert pos == sv.n_local
     assert max(d.rows * d.run for d in descs(plan, lv.LIST_DIRECT)) == 1 << 30
     assert info.bytes_read == info.bytes_written == 14 * sum(oracle.stage_view(spec, dst, 0, pp).n_local for pp in range(2))
+
+
+def test_many_buffers_split_into_passes():
+    """512 source and 128 target ranks: far more buffers than one launch can carry in its arguments, so the
+    lists are cut into several passes; the result must not change."""
+    spec = oracle.ModelSpec(n_layers=8, hidden=64, n_q_heads=8, n_kv_heads=8, ffn=64, vocab=64, tied_embed=True)
+    src, dst = oracle.Layout(8, 8, 8, 8), oracle.Layout(4, 4, 8, 8)
+    world = make_world(spec, src, synth.logical_state(oracle.logical_tensors(spec), 11, "uniform"))
+    plan, info, used = _check(spec, src, dst, world, 1 << 16)
+    assert info.n_src_bufs_used + info.n_dst_bufs_used > 2000          # > 400 per launch: several passes needed
