@@ -196,7 +196,7 @@ int liver_plan_desc(const liver_plan_t* plan, int list, int64_t i, liver_desc_t*
  * (0 = default: one per compute unit); tile_order 0 = each workgroup walks one
  * contiguous range of tiles, 1 = workgroups interleave tile by tile, 2 = groups
  * of up to 64 tiles visited in a scattered (multiplicative-permutation) order,
- * -1 = default (contiguous, except interleaved for direct launches below 48 GiB);
+ * -1 = default (contiguous);
  * cache_hints bit 0 = non-temporal loads, bit 1 = non-temporal stores, -1 =
  * default (direct: both; pack: loads only; unpack: stores only, so that the
  * staging chunk may stay cache-resident).  Not thread-safe against concurrent

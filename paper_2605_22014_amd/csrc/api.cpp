@@ -46,12 +46,11 @@ int run_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uin
         args.descs = (const liver::DevDesc*)((const char*)plan->dev_table + list.dev_offset) + pass.desc_begin;
         args.n_desc = pass.desc_count;
         args.n_tiles = pass.n_tiles;
-        // Tile order: measured on MI355X, one contiguous tile range per workgroup wins when a launch
-        // sweeps tens of GB spread over the whole HBM (7B direct reshard: 6.2 vs 5.9 TB/s) and for the
-        // chunk-sized pack / unpack launches; tile-by-tile interleaving wins by 4-8 % for direct launches
-        // of a few GB whose buffers sit close together (GPT-2-small, 13B and 70B single-rank shares).
-        const bool auto_interleave = &list == &plan->direct && pass.n_tiles < (48u << 14);  // < 48 GiB of 64 KiB tiles
-        args.tile_order = plan->tile_order >= 0 ? (uint32_t)plan->tile_order : (auto_interleave ? 1u : 0u);
+        // Tile order: one contiguous tile range per workgroup is the default.  Measured on MI355X it wins
+        // whenever the buffers are spread over the HBM (7B direct: 6.2 vs 5.9 TB/s; 13B share: 6.3 vs 5.7) and
+        // for the chunk-sized pack / unpack launches; tile-by-tile interleaving only wins (4-8 %) for
+        // launches of a few GB whose buffers all sit next to each other.
+        args.tile_order = plan->tile_order >= 0 ? (uint32_t)plan->tile_order : 0u;
         args.reserved = 0;
         // scattered order: groups of up to 64 tiles (4 MiB), at least ~32 groups per workgroup; the groups
         // are visited in a multiplicative permutation with a multiplier near 0.618 * n_groups
