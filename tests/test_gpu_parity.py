@@ -216,3 +216,34 @@ def test_many_buffers_split_into_passes():
     dev = to_dev(world)
     check_against(run_direct(plan, dev), want, plan, "direct, multi-pass")
     check_against(run_staged(plan, dev), want, plan, "staged")
+
+
+def test_staged_loop_in_hip_graph():
+    """The data calls are plain kernel launches (no allocation, no memset, no host sync), so a caller can
+    capture the whole pack / unpack loop in a HIP graph.  Replayed several times, with eager work and
+    synchronisation in between, every replay must reproduce the eager result."""
+    cfg, spec, src, dst = cfg_objects("tiny_gpt")
+    print("hip graph capture of the staged loop", flush=True)
+    world = make_world(spec, src, synth.logical_state(oracle.logical_tensors(spec), 8, "uniform"))
+    want = oracle.reshard_state(spec, src, dst, world)
+    plan = _plan(spec, src, dst, cfg["chunk_bytes"])
+    n = lv.liver_plan_info(plan).n_chunks
+    dev = to_dev(world)
+    out = alloc_dst(plan)
+    staging = torch.empty(cfg["chunk_bytes"], dtype=torch.uint8, device="cuda")
+    from paper_2605_22014_amd._binding import make_table
+    st, dt = make_table(dev, src.n_ranks), make_table(out, dst.n_ranks)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for c in range(n):
+            lv.liver_pack(plan, c, st, staging)
+            lv.liver_unpack(plan, c, staging, dt)
+        lv.liver_reshard(plan, st, dt)                  # the direct path too: same bytes again
+    for replay in range(3):
+        for t in out.values():
+            t.fill_(-7)                                  # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        check_against(out, want, plan, f"graph replay {replay}")
