@@ -156,7 +156,10 @@ class Plan:
         self.handle, self.src, self.dst, self.chunk_bytes = handle, src, dst, chunk_bytes
 
     def __del__(self):
-        liver_plan_destroy(self)
+        try:
+            liver_plan_destroy(self)
+        except Exception:       # interpreter shutdown: the library may already be gone
+            pass
 
 
 def liver_plan_create(spec: ModelSpec, src: Layout, dst: Layout, chunk_bytes: int) -> Plan:
