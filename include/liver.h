@@ -105,7 +105,13 @@ typedef struct {
     int32_t tp, pp, dp;
     int32_t pad_multiple;               /* flat buffers are padded to a multiple of dp*pad_multiple */
     int32_t only_tp, only_pp, only_dp;  /* target layout: -1 = every rank, else plan only the share of
-                                           the ranks with this coordinate.  Source layout: must be -1 */
+                                           the ranks with this coordinate.  Source layout: -1 = every
+                                           rank, else liver_pack and liver_reshard move only the pieces
+                                           READ from the ranks with this coordinate; the wire layout
+                                           and liver_unpack do not change, so chunks packed under
+                                           different source restrictions into one staging chunk
+                                           complement each other (one source GPU each, in a real
+                                           system).  Zero padding is written under every restriction */
     uint32_t flags;                     /* target layout: LIVER_DERIVE_BF16.  Source layout: 0 */
     uint32_t kind_mask;                 /* target layout: bit k set = buffer kind k takes part;
                                            0 = all four.  Source layout: 0 */
@@ -171,7 +177,7 @@ typedef struct {
  * UNSUPPORTED (layers do not split over the stages as asked, hidden % n_q_heads, n_q_heads % n_kv_heads,
  * ffn % tp non-zero, vocab % tp non-zero without vocab_multiple, kv heads neither split (n_kv_heads % tp == 0) nor
  * replicated evenly (tp % n_kv_heads == 0 and q heads per group % (tp/n_kv_heads) == 0); only_* out of
- * range or set on the source layout), NOMEM, HIP. */
+ * range), NOMEM, HIP. */
 int liver_plan_create(const liver_model_spec_t* spec, const liver_layout_t* src,
                       const liver_layout_t* dst, size_t chunk_bytes, liver_plan_t** out);
 

@@ -281,6 +281,13 @@ struct Builder {
 
     int rank_of(const liver_layout_t& lay, int tp, int pp, int dp) const { return tp + lay.tp * (dp + lay.dp * pp); }
     bool dst_dp_planned(int dp) const { return plan.dst.only_dp < 0 || plan.dst.only_dp == dp; }
+    // Source-side restriction: does the plan read from this source rank?  (pack and direct lists only; the
+    // wire layout and the unpack list do not depend on it)
+    bool src_planned(int rank) const {
+        const liver_layout_t& S = plan.src;
+        const int tp = rank % S.tp, dp = (rank / S.tp) % S.dp, pp = rank / (S.tp * S.dp);
+        return (S.only_tp < 0 || S.only_tp == tp) && (S.only_pp < 0 || S.only_pp == pp) && (S.only_dp < 0 || S.only_dp == dp);
+    }
     bool kind_on(int k) const { return plan.dst.kind_mask == 0 || ((plan.dst.kind_mask >> k) & 1u); }
 
     void push_bounded(Entry&& e) {  // keep every entry below 2^30 elements (32-bit unit counters)
@@ -421,8 +428,9 @@ int Builder::run() {
             return LIVER_E_UNSUPPORTED;
         }
     }
-    if (S.only_tp != -1 || S.only_pp != -1 || S.only_dp != -1 || S.flags || S.kind_mask) {
-        why = "source layout: only_* must be -1, flags and kind_mask 0";
+    if (S.only_tp < -1 || S.only_tp >= S.tp || S.only_pp < -1 || S.only_pp >= S.pp || S.only_dp < -1 ||
+        S.only_dp >= S.dp || S.flags || S.kind_mask) {
+        why = "source layout: only_* out of range, or flags / kind_mask not 0";
         return LIVER_E_UNSUPPORTED;
     }
     if (D.only_tp < -1 || D.only_tp >= D.tp || D.only_pp < -1 || D.only_pp >= D.pp || D.only_dp < -1 ||
@@ -591,7 +599,9 @@ void Builder::emit_lists() {
     i64 pos = 0;  // byte position on the stream
     std::vector<Entry> subs;
     for (const Entry& e : entries) {
-        for (const Dst& d : e.dsts) plan.direct.pub.push_back(pub(e, d, -1));
+        const bool read_here = e.src_rank < 0 || src_planned(e.src_rank);  // zero fills are always planned
+        if (read_here)
+            for (const Dst& d : e.dsts) plan.direct.pub.push_back(pub(e, d, -1));
         if (e.src_rank < 0) {  // zero fill: no wire bytes; belongs to the chunk the stream is in
             const i64 chunk = pos == 0 ? 0 : (pos - 1) / B;
             for (const Dst& d : e.dsts) plan.unpack.pub.push_back(pub(e, d, (int)chunk));
@@ -616,7 +626,7 @@ void Builder::emit_lists() {
                 pk.src_rank = s.src_rank, pk.src_kind = s.src_kind, pk.dst_rank = -1, pk.dst_kind = -1;
                 pk.src_off = s.src_off, pk.src_stride = s.src_stride;
                 pk.dst_off = wire_elem, pk.dst_stride = s.run, pk.rows = s.rows, pk.run = s.run;
-                plan.pack.pub.push_back(pk);
+                if (read_here) plan.pack.pub.push_back(pk);
                 for (const Dst& d : s.dsts) {
                     liver_desc_t un = pub(s, d, (int)chunk);
                     un.src_rank = -1;  // staging; src_kind keeps the wire element type

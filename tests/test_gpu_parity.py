@@ -247,3 +247,33 @@ def test_staged_loop_in_hip_graph():
         graph.replay()
         torch.cuda.synchronize()
         check_against(out, want, plan, f"graph replay {replay}")
+
+
+def test_source_side_restriction():
+    """One plan per source rank (what each source GPU would run): all of them pack their pieces of a chunk
+    into the same staging chunk, one unpack scatters it; their direct reshards together give the full result."""
+    cfg, spec, src, dst = cfg_objects("tiny_gpt")
+    print("source-side restriction", flush=True)
+    world = make_world(spec, src, synth.logical_state(oracle.logical_tensors(spec), 9, "uniform"))
+    want = oracle.reshard_state(spec, src, dst, world)
+    dev = to_dev(world)
+    s, a, b = lv_objects(spec, src, dst)
+    full = lv.liver_plan_create(s, a, b, cfg["chunk_bytes"])
+    plans = [lv.liver_plan_create(s, lv.Layout(src.tp, src.pp, src.dp, src.pad_multiple, only_tp=tp, only_pp=pp, only_dp=dp),
+                                  b, cfg["chunk_bytes"])
+             for tp in range(src.tp) for pp in range(src.pp) for dp in range(src.dp)]
+    out = alloc_dst(full)
+    for p in plans:
+        present = {k: t for k, t in dev.items() if lv.liver_plan_buffer_used(p, 0, k[0], k[1])}
+        lv.liver_reshard(p, present, out)                 # other ranks' buffers are not even passed
+    torch.cuda.synchronize()
+    check_against(out, want, full, "direct, union of source-restricted plans")
+    out = alloc_dst(full)
+    staging = torch.empty(cfg["chunk_bytes"], dtype=torch.uint8, device="cuda")
+    for c in range(lv.liver_plan_info(full).n_chunks):
+        staging.fill_(0x3C)
+        for p in plans:
+            lv.liver_pack(p, c, dev, staging)
+        lv.liver_unpack(plans[0], c, staging, out)
+    torch.cuda.synchronize()
+    check_against(out, want, full, "staged, packed by source-restricted plans")

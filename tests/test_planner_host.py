@@ -212,7 +212,7 @@ def test_error_codes():
         lv.liver_plan_create(s, a, lv.Layout(1, 2, 2, only_pp=2), 4096)
     assert e.value.code == -2
     with pytest.raises(lv.LiverError) as e:
-        lv.liver_plan_create(s, lv.Layout(2, 1, 2, only_tp=0), b, 4096)
+        lv.liver_plan_create(s, lv.Layout(2, 1, 2, only_tp=2), b, 4096)
     assert e.value.code == -2
     for bad in (lv.Layout(1, 2, 2, pp_first=3), lv.Layout(1, 2, 2, vpp=2), lv.Layout(1, 2, 2, pp_first=1, vpp=1, pp_last=2),
                 lv.Layout(8, 1, 1), lv.Layout(1, 1, 1, vocab_multiple=-1)):
@@ -280,3 +280,58 @@ def test_many_buffers_split_into_passes():
     world = make_world(spec, src, synth.logical_state(oracle.logical_tensors(spec), 11, "uniform"))
     plan, info, used = _check(spec, src, dst, world, 1 << 16)
     assert info.n_src_bufs_used + info.n_dst_bufs_used > 2000          # > 400 per launch: several passes needed
+
+
+def test_source_side_restriction_partitions_the_work():
+    """Plans restricted to one source rank each (what one source GPU would run): their pack lists fill
+    disjoint parts of every staging chunk and together the whole payload; their direct lists together write
+    every target element exactly once (zero padding: once per plan); unpack does not depend on the restriction."""
+    spec = ODD
+    src, dst = oracle.Layout(2, 2, 2, 4), oracle.Layout(1, 2, 3, 1)
+    world = make_world(spec, src, tiny_state(spec, seed=77))
+    want = oracle.reshard_state(spec, src, dst, world)
+    s, a, b = lv_objects(spec, src, dst)
+    full = lv.liver_plan_create(s, a, b, 512)
+    info = lv.liver_plan_info(full)
+    plans = []
+    for tp in range(src.tp):
+        for pp in range(src.pp):
+            for dp in range(src.dp):
+                a1 = lv.Layout(src.tp, src.pp, src.dp, src.pad_multiple, only_tp=tp, only_pp=pp, only_dp=dp)
+                plans.append(lv.liver_plan_create(s, a1, b, 512))
+    from interp import alloc_dst, execute
+    # direct: union of the restricted plans
+    out, counts = alloc_dst(full)
+    for p in plans:
+        i = lv.liver_plan_info(p)
+        assert (i.n_chunks, i.stream_bytes) == (info.n_chunks, info.stream_bytes)
+        assert [(d.op, d.chunk, d.src_off, d.dst_rank, d.dst_kind, d.dst_off, d.rows, d.run) for d in descs(p, lv.LIST_UNPACK)] == \
+            [(d.op, d.chunk, d.src_off, d.dst_rank, d.dst_kind, d.dst_off, d.rows, d.run) for d in descs(full, lv.LIST_UNPACK)]
+        for d in descs(p, lv.LIST_DIRECT):
+            execute(d, world, out, counts)
+    pad = {key: np.zeros_like(c, bool) for key, c in counts.items()}
+    for d in descs(full, lv.LIST_DIRECT):
+        if d.op == lv.OP_ZERO:
+            pad[(d.dst_rank, d.dst_kind)][d.dst_off:d.dst_off + d.run] = True
+    for key in out:
+        assert np.array_equal(out[key], want[key]), key
+        assert (counts[key][~pad[key]] == 1).all() and (counts[key][pad[key]] == len(plans)).all(), key
+    # staged: every source rank packs its pieces into the same chunk; then one unpack
+    out, counts = alloc_dst(full)
+    un = {}
+    for d in descs(full, lv.LIST_UNPACK):
+        un.setdefault(d.chunk, []).append(d)
+    for c in range(info.n_chunks):
+        staging = np.full(512, 0x3C, np.uint8)
+        covered = np.zeros(512, np.uint8)
+        for p in plans:
+            for d in descs(p, lv.LIST_PACK):
+                if d.chunk == c:
+                    execute(d, world, None, None, staging)
+                    eb = 2 if d.src_kind == 0 else 4
+                    covered[d.dst_off * eb:(d.dst_off + d.rows * d.run) * eb] += 1
+        assert covered.max() == 1
+        for d in un[c]:
+            execute(d, None, out, counts, staging)
+    for key in out:
+        assert np.array_equal(out[key], want[key]) and (counts[key] == 1).all(), key
