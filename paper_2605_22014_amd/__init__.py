@@ -10,4 +10,6 @@ from ._binding import (ADAM_M, ADAM_V, MASTER, PARAM, LiverError, Layout, ModelS
                        liver_plan_desc, liver_plan_desc_count, liver_plan_destroy, liver_plan_info,
                        liver_plan_set_launch, liver_reshard, liver_reshard_staged, liver_debug_emulate_host, liver_strerror, liver_unpack, library_path)
 
+from .generation import GenerationManager, GenerationError, State  # noqa: E402
+
 __all__ = [n for n in dir() if not n.startswith("_")]
