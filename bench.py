@@ -246,6 +246,7 @@ def cpu_baseline(cfg, src_bufs, dst_bufs, src, dst, n_layers_sampled=8):
         host = {}                       # host copies of the source ranges that hold this layer
         for tp in range(osrc.tp):
             sv = oracle.stage_view(ospec, osrc, tp, pp_src)
+            assert len(sv.buckets) == 1, "the benchmark configurations use one bucket per rank column"
             ps = [p for p in sv.params if p.name.startswith(f"L{layer}.")]
             lo, hi = min(p.offset for p in ps), max(p.offset + p.size for p in ps)
             for d in range(osrc.dp):

@@ -18,7 +18,13 @@ NP = {0: np.uint16, 1: np.uint32, 2: np.uint32, 3: np.uint32}
 
 
 def _setup(name):
-    cfg, ospec, osrc, odst = cfg_objects(name)
+    if isinstance(name, dict):
+        cfg = name
+        ospec = oracle.ModelSpec(**cfg["spec"])
+        osrc = oracle.Layout(pad_multiple=cfg["pad_multiple"], **cfg["src"])
+        odst = oracle.Layout(pad_multiple=cfg["pad_multiple"], **cfg["dst"])
+    else:
+        cfg, ospec, osrc, odst = cfg_objects(name)
     only = cfg["only"] or {}
     spec = lv.ModelSpec(**cfg["spec"])
     src = lv.Layout(pad_multiple=cfg["pad_multiple"], **cfg["src"])
@@ -74,37 +80,42 @@ def _compare(expected, only, odst, dst_bufs, what):
     n_checked = 0
     for k, tp, pp, sv, prm, shard in expected:
         flat = shard.ravel()
-        for d in range(odst.dp):
+        if k == 0:
+            pieces = [(d, prm.offset, prm.offset, prm.size) for d in range(odst.dp)]      # every replica, whole shard
+        else:
+            pieces = oracle.dp_pieces(sv, odst, prm.offset, prm.offset + prm.size)         # (dp, local, flat, n)
+        for d, local, at, n in pieces:
             if only.get("dp", d) != d:
                 continue
-            r = odst.rank(tp, pp, d)
-            if k == 0:
-                a, b, part = prm.offset, prm.offset + prm.size, flat
-            else:
-                lo, hi = max(prm.offset, d * sv.S), min(prm.offset + prm.size, (d + 1) * sv.S)
-                if lo >= hi:
-                    continue
-                part, a, b = flat[lo - prm.offset:hi - prm.offset], lo - d * sv.S, hi - d * sv.S
-            got = dst_bufs[(r, k)][a:b].cpu().numpy().view(NP[k])
-            assert np.array_equal(got, part), (what, prm.name, "rank", r, "kind", k)
-            n_checked += part.size
+            got = dst_bufs[(odst.rank(tp, pp, d), k)][local:local + n].cpu().numpy().view(NP[k])
+            assert np.array_equal(got, flat[at - prm.offset:at - prm.offset + n]), (what, prm.name, "dp", d, "kind", k)
+            n_checked += n
     assert n_checked > 0
     return n_checked
 
 
 def _pads_zero(only, ospec, odst, dst_bufs):
+    """Every padding element of the planned target buffers is +0: the tail of each bucket, wherever it lives."""
     for (r, k), t in dst_bufs.items():
-        pp = r // (odst.tp * odst.dp)
-        d = (r // odst.tp) % odst.dp
+        pp, d = r // (odst.tp * odst.dp), (r // odst.tp) % odst.dp
         sv = oracle.stage_view(ospec, odst, r % odst.tp, pp)
-        lo = sv.n_local if k == 0 else max(sv.n_local - d * sv.S, 0)
-        if lo < t.numel():
-            assert not t[lo:].any().item(), ("padding not zero", r, k)
+        ends = sorted(p.offset + p.size for p in sv.params)
+        for b0, nb in sv.buckets:
+            used_end = max(e for e in ends if e <= b0 + nb)
+            if used_end == b0 + nb:
+                continue
+            if k == 0:
+                assert not t[used_end:b0 + nb].any().item(), ("padding not zero", r, k)
+            else:
+                for dd, local, _, n in oracle.dp_pieces(sv, odst, used_end, b0 + nb):
+                    if dd == d:
+                        assert not t[local:local + n].any().item(), ("padding not zero", r, k)
 
 
 def _run(name, names):
+    name, cfg_or_name = (name["name"], name) if isinstance(name, dict) else (name, name)
     print(f"{name}: generating state in HBM", flush=True)
-    cfg, only, ospec, osrc, odst, plan, src, dst, src_bufs = _setup(name)
+    cfg, only, ospec, osrc, odst, plan, src, dst, src_bufs = _setup(cfg_or_name)
     sums = {key: int(t.view(torch.int16 if key[1] == 0 else torch.int32).sum(dtype=torch.int64)) for key, t in src_bufs.items()}
     info = lv.liver_plan_info(plan)
     print(f"{name}: direct reshard, {info.n_desc} descriptors, {(info.bytes_read + info.bytes_written) / 1e9:.2f} GB", flush=True)
@@ -152,3 +163,15 @@ def test_llama70b_one_target_rank():
     _, ospec, _, _ = cfg_objects("llama70b_rank")
     names = _layer(ospec, 30) + _layer(ospec, 39, ("q.w", "k.w", "v.w", "o.w", "ln2.w"))
     _run("llama70b_rank", names)
+
+
+def test_llama7b_layout_variants_at_full_size():
+    """The 7B shape with every layout variant switched on: vocabulary padded per world (32000 -> 32768 rows),
+    40 M-element buckets, interleaved stages on the target, DP 1 -> 2 (bucket-wise DP slices), derived bf16."""
+    cfg = dict(synth.CONFIGS["llama7b"], name="llama7b variants",
+               src=dict(tp=8, pp=1, dp=1, vocab_multiple=128, bucket_elems=40_000_000),
+               dst=dict(tp=4, pp=2, dp=2, vpp=2, vocab_multiple=128, bucket_elems=40_000_000), kinds=(0, 1, 2, 3))
+    ospec = oracle.ModelSpec(**cfg["spec"])
+    names = ["embed.word", "lm_head.w", "final_norm.w"] + _layer(ospec, 0, ("q.w", "k.w", "v.w", "o.w", "ln1.w")) \
+        + _layer(ospec, 8, ("gate.w", "down.w")) + _layer(ospec, 23, ("up.w", "o.w", "ln2.w")) + _layer(ospec, 31, ("down.w", "q.w"))
+    _run(cfg, names)
