@@ -59,8 +59,8 @@
  *     copy with the lowest coordinate (dp = 0, tp = 0, first stage); source
  *     padding is never read; target padding is written +0.
  *
- * Buffer tables: src_bufs[rank*4 + kind], dst_bufs[rank*4 + kind] are DEVICE
- * pointers, rank = tp + TP*(dp + DP*pp).  Entries the plan does not use
+ * Buffer tables: src_bufs[rank*LIVER_NUM_KINDS + kind], dst_bufs[rank*LIVER_NUM_KINDS
+ * + kind] are DEVICE pointers, rank = tp + TP*(dp + DP*pp).  Entries the plan does not use
  * (liver_plan_buffer_used == 0) may be NULL.  The tables themselves are HOST
  * arrays, read before the call returns.
  *
@@ -79,8 +79,12 @@ extern "C" {
 
 typedef struct liver_plan liver_plan_t; /* opaque, owned by the library */
 
+/* Buffer kinds.  0..3: the dense parameters of a rank.  4..7: the same four kinds for the EXPERT parameters
+ * of a mixture-of-experts model (n_experts > 0), which live in buffers of their own because they are
+ * replicated and optimizer-sharded over a different group of ranks (see liver_layout_t.ep). */
 enum { LIVER_PARAM_BF16 = 0, LIVER_MASTER_F32 = 1, LIVER_ADAM_M_F32 = 2, LIVER_ADAM_V_F32 = 3,
-       LIVER_NUM_KINDS = 4 };
+       LIVER_EXPERT_PARAM_BF16 = 4, LIVER_EXPERT_MASTER_F32 = 5, LIVER_EXPERT_ADAM_M_F32 = 6,
+       LIVER_EXPERT_ADAM_V_F32 = 7, LIVER_NUM_KINDS = 8 };
 
 /* liver_model_spec_t.flags */
 enum { LIVER_GLU = 1u,         /* gated FFN: gate.w + up.w (SwiGLU); else a plain 2-layer MLP */

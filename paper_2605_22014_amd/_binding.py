@@ -2,7 +2,7 @@
 
 The functions keep the names of the C entry points.  Buffer tables are given as
 {(rank, kind): tensor-or-address} dictionaries (or a ready ctypes array) and are
-marshalled into the rank*4+kind pointer tables the library expects.
+marshalled into the rank*NUM_KINDS+kind pointer tables the library expects.
 """
 from __future__ import annotations
 
@@ -19,6 +19,8 @@ from typing import Dict, Optional, Tuple
 import torch  # noqa: F401
 
 PARAM, MASTER, ADAM_M, ADAM_V = 0, 1, 2, 3
+EXPERT_PARAM, EXPERT_MASTER, EXPERT_ADAM_M, EXPERT_ADAM_V = 4, 5, 6, 7     # expert parameters of MoE models
+NUM_KINDS = 8                                                             # stride of the buffer tables
 LIST_DIRECT, LIST_PACK, LIST_UNPACK = 0, 1, 2
 OP_COPY, OP_CAST_BF16, OP_ZERO = 0, 1, 2
 _GLU, _NORM_BIAS, _LINEAR_BIAS, _TIED = 1, 2, 4, 8
@@ -220,12 +222,12 @@ def _addr(x) -> int:
 
 
 def _table(bufs, n_ranks: int):
-    """{(rank, kind): tensor | address} -> void*[n_ranks*4]."""
+    """{(rank, kind): tensor | address} -> void*[n_ranks*NUM_KINDS]."""
     if not isinstance(bufs, dict):
         return bufs               # already a ctypes array
-    arr = (C.c_void_p * (n_ranks * 4))()
+    arr = (C.c_void_p * (n_ranks * NUM_KINDS))()
     for (rank, kind), t in bufs.items():
-        arr[rank * 4 + kind] = _addr(t)
+        arr[rank * NUM_KINDS + kind] = _addr(t)
     return arr
 
 
@@ -258,9 +260,9 @@ def liver_reshard_staged(plan: Plan, src_bufs, dst_bufs, staging, stream_pack=No
 def liver_debug_emulate_host(plan: Plan, which: int, chunk: int, src_bufs, dst_bufs, staging) -> None:
     """Run the lowered descriptors on HOST arrays ({(rank, kind): numpy array}); test aid."""
     def table(bufs, n):
-        arr = (C.c_void_p * (n * 4))()
+        arr = (C.c_void_p * (n * NUM_KINDS))()
         for (rank, kind), a in (bufs or {}).items():
-            arr[rank * 4 + kind] = a.ctypes.data
+            arr[rank * NUM_KINDS + kind] = a.ctypes.data
         return arr
     _check(_lib.liver_debug_emulate_host(plan.handle, which, chunk, table(src_bufs, plan.src.n_ranks),
                                          table(dst_bufs, plan.dst.n_ranks),

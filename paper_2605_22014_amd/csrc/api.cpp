@@ -29,8 +29,8 @@ int run_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uin
         return fail(LIVER_E_INVALID_ARG, "current HIP device is not the one the plan was created on");
     for (uint32_t p = p0; p < p1; ++p)
         for (const liver::BufRef& r : list.passes[p].bufs) {
-            const void* ptr = r.side == 0   ? (src_bufs ? src_bufs[(size_t)r.rank * 4 + r.kind] : nullptr)
-                              : r.side == 1 ? (dst_bufs ? dst_bufs[(size_t)r.rank * 4 + r.kind] : nullptr)
+            const void* ptr = r.side == 0   ? (src_bufs ? src_bufs[(size_t)r.rank * LIVER_NUM_KINDS + r.kind] : nullptr)
+                              : r.side == 1 ? (dst_bufs ? dst_bufs[(size_t)r.rank * LIVER_NUM_KINDS + r.kind] : nullptr)
                                             : staging;
             if (!ptr) return fail(LIVER_E_INVALID_ARG, "a buffer the plan uses is NULL");
             if ((uintptr_t)ptr % 16) return fail(LIVER_E_INVALID_ARG, "buffers must be 16-byte aligned");
@@ -67,8 +67,8 @@ int run_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uin
         }
         size_t i = 0;
         for (const liver::BufRef& r : pass.bufs) {
-            const void* ptr = r.side == 0 ? src_bufs[(size_t)r.rank * 4 + r.kind]
-                              : r.side == 1 ? dst_bufs[(size_t)r.rank * 4 + r.kind] : staging;
+            const void* ptr = r.side == 0 ? src_bufs[(size_t)r.rank * LIVER_NUM_KINDS + r.kind]
+                              : r.side == 1 ? dst_bufs[(size_t)r.rank * LIVER_NUM_KINDS + r.kind] : staging;
             args.bufs[i++] = (char*)ptr;
         }
         for (; i < (size_t)liver::MAX_PASS_BUFS; ++i) args.bufs[i] = nullptr;
@@ -145,6 +145,10 @@ int liver_plan_buffer_bytes(const liver_plan_t* plan, int side, int rank, int ki
     if (rank < 0 || rank >= n_ranks(lay)) return fail(LIVER_E_INVALID_ARG, "rank out of range");
     const int pp = rank / (lay.tp * lay.dp);
     const liver::StageSize& st = (side ? plan->dst_stage : plan->src_stage)[pp];
+    if (kind >= LIVER_EXPERT_PARAM_BF16) {  // expert buffers exist only for mixture-of-experts models
+        *out = 0;
+        return LIVER_OK;
+    }
     *out = kind == LIVER_PARAM_BF16 ? (size_t)st.n_pad * 2 : (size_t)st.S * 4;
     return LIVER_OK;
 }
@@ -153,7 +157,7 @@ int liver_plan_buffer_used(const liver_plan_t* plan, int side, int rank, int kin
     if (!plan || side < 0 || side > 1 || kind < 0 || kind >= LIVER_NUM_KINDS)
         return fail(LIVER_E_INVALID_ARG, "bad argument");
     if (rank < 0 || rank >= n_ranks(side ? plan->dst : plan->src)) return fail(LIVER_E_INVALID_ARG, "rank out of range");
-    return plan->used[side][(size_t)rank * 4 + kind];
+    return plan->used[side][(size_t)rank * LIVER_NUM_KINDS + kind];
 }
 
 int64_t liver_plan_desc_count(const liver_plan_t* plan, int list) {

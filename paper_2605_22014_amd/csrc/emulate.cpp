@@ -57,8 +57,8 @@ extern "C" int liver_debug_emulate_host(const liver_plan_t* plan, int list_id, i
                 if (idx >= pass.bufs.size()) return nullptr;
                 const BufRef& r = pass.bufs[idx];
                 cap = buffer_bytes(plan, r);
-                const void* p = r.side == 0   ? (src_bufs ? src_bufs[(size_t)r.rank * 4 + r.kind] : nullptr)
-                                : r.side == 1 ? (dst_bufs ? dst_bufs[(size_t)r.rank * 4 + r.kind] : nullptr)
+                const void* p = r.side == 0   ? (src_bufs ? src_bufs[(size_t)r.rank * LIVER_NUM_KINDS + r.kind] : nullptr)
+                                : r.side == 1 ? (dst_bufs ? dst_bufs[(size_t)r.rank * LIVER_NUM_KINDS + r.kind] : nullptr)
                                               : staging;
                 return (char*)p;
             };

@@ -91,7 +91,7 @@ struct liver_plan {
     std::vector<liver::StageSize> src_stage, dst_stage;  // per pp
     liver::List direct, pack, unpack;
     liver_plan_info_t info{};
-    std::vector<uint8_t> used[2];  // [side][rank*4+kind]
+    std::vector<uint8_t> used[2];  // [side][rank*LIVER_NUM_KINDS+kind]
     // device side
     void* dev_table = nullptr;
     int device = -1;

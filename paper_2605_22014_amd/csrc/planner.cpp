@@ -563,12 +563,12 @@ int Builder::run() {
     info.n_desc_unpack = (i64)plan.unpack.pub.size();
     info.n_src_ranks = S.tp * S.pp * S.dp;
     info.n_dst_ranks = D.tp * D.pp * D.dp;
-    plan.used[0].assign((size_t)info.n_src_ranks * 4, 0);
-    plan.used[1].assign((size_t)info.n_dst_ranks * 4, 0);
+    plan.used[0].assign((size_t)info.n_src_ranks * LIVER_NUM_KINDS, 0);
+    plan.used[1].assign((size_t)info.n_dst_ranks * LIVER_NUM_KINDS, 0);
     for (const liver_desc_t& d : plan.direct.pub) {
-        if (d.op != LIVER_OP_ZERO) plan.used[0][(size_t)d.src_rank * 4 + d.src_kind] = 1;
+        if (d.op != LIVER_OP_ZERO) plan.used[0][(size_t)d.src_rank * LIVER_NUM_KINDS + d.src_kind] = 1;
         else info.pad_bytes += d.rows * d.run * elem_bytes(d.dst_kind);
-        plan.used[1][(size_t)d.dst_rank * 4 + d.dst_kind] = 1;
+        plan.used[1][(size_t)d.dst_rank * LIVER_NUM_KINDS + d.dst_kind] = 1;
     }
     info.bytes_read = plan.direct.hbm_read;        // a piece that feeds a fused copy + cast is read once
     info.bytes_written = plan.direct.hbm_written;
