@@ -55,6 +55,9 @@
  *     optimizer).  With bucket_elems > 0 this holds per bucket (see
  *     liver_layout_t): padding sits at the end of every bucket and a DP rank
  *     holds the d-th DP-th of every bucket, concatenated;
+ *   - mixture-of-experts models (n_experts > 0) keep router weights in the dense
+ *     buffers and the experts' FFN weights in a second set of buffers per rank
+ *     (kinds 4..7), see liver_layout_t.ep;
  *   - a value that exists several times in the source world is read from the
  *     copy with the lowest coordinate (dp = 0, tp = 0, first stage); source
  *     padding is never read; target padding is written +0.
@@ -103,6 +106,9 @@ typedef struct {
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, ffn, vocab;
     int32_t max_pos;   /* rows of the learned position embedding; 0 = none */
     uint32_t flags;    /* LIVER_GLU | LIVER_NORM_BIAS | LIVER_LINEAR_BIAS | LIVER_TIED_EMBED */
+    int32_t n_experts; /* > 0: mixture of experts.  Every layer's FFN is a router (router.w [n_experts, hidden],
+                          a dense parameter replicated over TP) plus n_experts FFNs of hidden size `ffn`, whose
+                          parameters live in the expert buffers (kinds 4..7).  0 = dense model */
 } liver_model_spec_t;
 
 typedef struct {
@@ -117,8 +123,8 @@ typedef struct {
                                            complement each other (one source GPU each, in a real
                                            system).  Zero padding is written under every restriction */
     uint32_t flags;                     /* target layout: LIVER_DERIVE_BF16.  Source layout: 0 */
-    uint32_t kind_mask;                 /* target layout: bit k set = buffer kind k takes part;
-                                           0 = all four.  Source layout: 0 */
+    uint32_t kind_mask;                 /* target layout: bit k (0..3) set = kinds k and k+4 take part;
+                                           0 = all.  Source layout: 0 */
     int32_t vpp;                        /* model chunks per pipeline stage (interleaved schedule);
                                            0 or 1 = none.  The layers are cut into pp*vpp groups and
                                            stage p holds groups p, p+pp, p+2*pp, ... in that order */
@@ -136,6 +142,15 @@ typedef struct {
                                            to a multiple of dp*pad_multiple and split evenly over DP, and
                                            a DP rank's fp32 buffer is the concatenation of its slices.
                                            0 = one bucket */
+    int32_t ep;                         /* expert-parallel size (0 or 1 = none; must divide dp and
+                                           n_experts).  DP rank d has expert-parallel index d % ep and holds
+                                           experts [e*E/ep, (e+1)*E/ep) of its stage, each split over TP like
+                                           a dense FFN.  A rank's expert buffer lists them layer by layer,
+                                           expert by expert (fc1, fc2 with their biases), under the same
+                                           bucket / padding rules with dp/ep in place of dp; it is replicated
+                                           (bf16) and optimizer-sharded (fp32) over the dp/ep ranks with the
+                                           same index, in ascending order; the first of them is the copy
+                                           that is read.  Dense buffers do not depend on ep */
 } liver_layout_t;
 
 typedef struct {

@@ -63,6 +63,17 @@ Megatron-style mixed-parallel training, stated so a reader can check it by eye):
       holds V_p/TP rows; rows with global index >= V are padding: written +0 in
       the target, never read from the source.  Logical tensors keep V rows.
   R12 buffer-table index of a rank is tp + TP*(dp + DP*pp).
+  R13 mixture of experts (n_experts = E > 0; the paper's Appendix A.2.3 extends the
+      view "to the expert dimension"): every layer's FFN becomes a router
+      (router.w [E, H], a dense parameter replicated over TP) plus E experts with
+      their own gate/up/down weights.  With expert parallelism EP (EP divides DP
+      and E) DP rank d belongs to expert-parallel index d % EP and holds experts
+      [ep*E/EP, (ep+1)*E/EP) of its stage, each split over TP like a dense FFN.
+      Expert parameters form a SECOND flat buffer per rank (kinds 4..7), laid out
+      layer by layer, expert by expert (fc1, fc2), with the same bucket / padding
+      rules, but replicated and optimizer-sharded over the DP/EP ranks that hold
+      the same experts (d = ep, ep + EP, ...), in that order; the copy that is read
+      is the first of them.  Dense parameters (kinds 0..3) are unaffected by EP.
 
 All data are handled as raw bit patterns (uint16 for bf16, uint32 for fp32):
 resharding moves bits, it never interprets them (except rne_bf16).
@@ -81,7 +92,10 @@ import numpy as np
 
 PARAM, MASTER, ADAM_M, ADAM_V = 0, 1, 2, 3
 KINDS = (PARAM, MASTER, ADAM_M, ADAM_V)
-WORD = {PARAM: np.uint16, MASTER: np.uint32, ADAM_M: np.uint32, ADAM_V: np.uint32}
+# R13: the expert parameters of a mixture-of-experts model live in buffers of their own, kinds 4..7
+EXPERT_PARAM, EXPERT_MASTER, EXPERT_ADAM_M, EXPERT_ADAM_V = 4, 5, 6, 7
+EXPERT_KINDS = (EXPERT_PARAM, EXPERT_MASTER, EXPERT_ADAM_M, EXPERT_ADAM_V)
+WORD = {k: (np.uint16 if k % 4 == 0 else np.uint32) for k in range(8)}
 
 
 @dataclass(frozen=True)
@@ -97,6 +111,7 @@ class ModelSpec:
     norm_bias: bool = False   # LayerNorm (with bias) instead of RMSNorm
     linear_bias: bool = False
     tied_embed: bool = False  # no lm_head; output layer reuses embed.word
+    n_experts: int = 0        # R13: > 0 = mixture of experts (ffn = hidden size of ONE expert's FFN)
 
 
 @dataclass(frozen=True)
@@ -110,6 +125,7 @@ class Layout:
     pp_first: int = 0         # R9c: layers on the first / last stage (0 = even share); the other
     pp_last: int = 0          #      stages split the remaining layers evenly
     bucket_elems: int = 0     # R5b: flat buffer cut into buckets of at least this many elements (0 = one bucket)
+    ep: int = 1               # R13: expert-parallel size (divides DP and n_experts)
 
     @property
     def n_ranks(self) -> int:
@@ -138,8 +154,9 @@ def check_supported(spec: ModelSpec, lay: Layout) -> None:
     ok = (lay.vpp >= 1 and _stage_counts(spec, lay) is not None and spec.hidden % spec.n_q_heads == 0
           and spec.n_q_heads % spec.n_kv_heads == 0 and _kv_split_ok(spec, lay.tp)
           and spec.ffn % lay.tp == 0 and (spec.vocab % lay.tp == 0 or lay.vocab_multiple > 0)
-          and lay.vocab_multiple >= 0
-          and min(lay.tp, lay.pp, lay.dp, lay.pad_multiple) >= 1)
+          and lay.vocab_multiple >= 0 and lay.bucket_elems >= 0
+          and min(lay.tp, lay.pp, lay.dp, lay.pad_multiple, lay.ep) >= 1
+          and ((lay.dp % lay.ep == 0 and spec.n_experts % lay.ep == 0) if spec.n_experts else lay.ep == 1))
     if not ok:
         raise ValueError(f"unsupported combination {spec} {lay}")
 
@@ -167,16 +184,19 @@ def logical_tensors(spec: ModelSpec) -> Dict[str, Tuple[int, ...]]:
         t[p + "ln2.w"] = (H,)
         if spec.norm_bias:
             t[p + "ln2.b"] = (H,)
-        if spec.glu:
-            t[p + "gate.w"] = (F, H)
-        t[p + "up.w"] = (F, H)
-        if spec.linear_bias:
+        if spec.n_experts:                           # R13: router + one FFN per expert
+            t[p + "router.w"] = (spec.n_experts, H)
+        for q in ([p + f"x{e}." for e in range(spec.n_experts)] if spec.n_experts else [p]):
             if spec.glu:
-                t[p + "gate.b"] = (F,)
-            t[p + "up.b"] = (F,)
-        t[p + "down.w"] = (H, F)
-        if spec.linear_bias:
-            t[p + "down.b"] = (H,)
+                t[q + "gate.w"] = (F, H)
+            t[q + "up.w"] = (F, H)
+            if spec.linear_bias:
+                if spec.glu:
+                    t[q + "gate.b"] = (F,)
+                t[q + "up.b"] = (F,)
+            t[q + "down.w"] = (H, F)
+            if spec.linear_bias:
+                t[q + "down.b"] = (H,)
     t["final_norm.w"] = (H,)
     if spec.norm_bias:
         t["final_norm.b"] = (H,)
@@ -214,8 +234,9 @@ class StageView:
     params: List[PhysParam]
     n_local: int              # end of the last parameter (interior bucket padding included)
     n_pad: int
-    S: int                    # elements of one DP rank's fp32 buffers = N_pad / DP
+    S: int                    # elements of one DP rank's fp32 buffers = N_pad / len(dp_ranks)
     buckets: List[Tuple[int, int]] = field(default_factory=list)   # (start, padded size) in flat coordinates
+    dp_ranks: List[int] = field(default_factory=list)   # DP coordinates sharing this flat buffer, in slice order
 
 
 def _rows(a: int, b: int) -> Tuple[slice, ...]:
@@ -257,8 +278,10 @@ def stage_layers(spec: ModelSpec, lay: Layout, pp: int) -> List[int]:
     return [l for v in range(lay.vpp) for l in range((v * lay.pp + pp) * c, (v * lay.pp + pp + 1) * c)]
 
 
-def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int) -> StageView:
-    """Ordered physical parameters of rank column (tp, pp) -- R2..R5, R8, R9."""
+def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int, ep: Optional[int] = None) -> StageView:
+    """Ordered physical parameters of rank column (tp, pp) -- R2..R5, R8, R9.
+    ep = None: the dense parameters (kinds 0..3).  ep = e: the expert parameters (kinds 4..7) held by the
+    ranks of expert-parallel index e (R13)."""
     check_supported(spec, lay)
     shapes = logical_tensors(spec)
     TP = lay.tp
@@ -306,16 +329,31 @@ def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int) -> StageView:
                 row += n
         out.append(PhysParam(p + "qkv." + suffix, (row,) + tail, blocks, True))
 
-    def fc1(p: str, suffix: str) -> None:            # R4
+    def fc1(p: str, suffix: str, phys: str) -> None:  # R4
         if not spec.glu:
-            split0(p + "fc1." + suffix, p + "up." + suffix)
+            split0(phys + "fc1." + suffix, p + "up." + suffix)
             return
         n = spec.ffn // TP
         tail = shapes[p + "up." + suffix][1:]
-        out.append(PhysParam(p + "fc1." + suffix, (2 * n,) + tail,
+        out.append(PhysParam(phys + "fc1." + suffix, (2 * n,) + tail,
                              [Block(p + "gate." + suffix, _rows(tp * n, (tp + 1) * n), _rows(0, n)),
                               Block(p + "up." + suffix, _rows(tp * n, (tp + 1) * n), _rows(n, 2 * n))],
                              True))
+
+    def ffn(p: str, phys: str) -> None:              # fc1 (+bias), fc2 (+bias) of the FFN whose tensors start with p
+        fc1(p, "w", phys)
+        if spec.linear_bias:
+            fc1(p, "b", phys)
+        split1(phys + "fc2.w", p + "down.w")
+        if spec.linear_bias:
+            replicated(p + "down.b")
+
+    if ep is not None:                               # R13: expert buffer: layer by layer, expert by expert
+        per = spec.n_experts // lay.ep
+        for l in stage_layers(spec, lay, pp):
+            for e in range(ep * per, (ep + 1) * per):
+                ffn(f"L{l}.x{e}.", f"L{l}.x{e}.")
+        return _finish(out, lay, [ep + lay.ep * j for j in range(lay.dp // lay.ep)])
 
     if pp == 0:
         vocab_split("embed.word", "embed.word")
@@ -335,12 +373,10 @@ def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int) -> StageView:
         replicated(p + "ln2.w")
         if spec.norm_bias:
             replicated(p + "ln2.b")
-        fc1(p, "w")
-        if spec.linear_bias:
-            fc1(p, "b")
-        split1(p + "fc2.w", p + "down.w")
-        if spec.linear_bias:
-            replicated(p + "down.b")
+        if spec.n_experts:
+            replicated(p + "router.w")
+        else:
+            ffn(p, p)
     if pp == lay.pp - 1:
         replicated("final_norm.w")
         if spec.norm_bias:
@@ -350,7 +386,12 @@ def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int) -> StageView:
         elif lay.pp > 1:                             # R8: second copy, never the one read
             vocab_split("embed.word(tied copy)", "embed.word", canonical=False)
 
-    quantum = lay.dp * lay.pad_multiple              # R6
+    return _finish(out, lay, list(range(lay.dp)))
+
+
+def _finish(out: List[PhysParam], lay: Layout, dp_ranks: List[int]) -> StageView:
+    """Assign flat offsets (R5), close and pad buckets (R5b, R6)."""
+    quantum = len(dp_ranks) * lay.pad_multiple       # R6
     buckets: List[Tuple[int, int]] = []
     off = start = end = 0
     for i, prm in enumerate(out):                    # R5: back to back, no per-param padding
@@ -360,12 +401,24 @@ def stage_view(spec: ModelSpec, lay: Layout, tp: int, pp: int) -> StageView:
             off = start + -(-(off - start) // quantum) * quantum
             buckets.append((start, off - start))
             start = off
-    return StageView(out, end, off, off // lay.dp, buckets)
+    return StageView(out, end, off, off // len(dp_ranks), buckets, dp_ranks)
 
 
-def buffer_elems(spec: ModelSpec, lay: Layout, tp: int, pp: int, kind: int) -> int:
-    sv = stage_view(spec, lay, tp, pp)
-    return sv.n_pad if kind == PARAM else sv.S
+def kinds_of(spec: ModelSpec) -> Tuple[int, ...]:
+    return KINDS + EXPERT_KINDS if spec.n_experts else KINDS
+
+
+def columns(lay: Layout, kind: int):
+    """(tp, pp, ep) of every flat buffer of `kind`: ep is None for the dense kinds."""
+    for pp in range(lay.pp):
+        for tp in range(lay.tp):
+            for ep in (range(lay.ep) if kind >= EXPERT_PARAM else (None,)):
+                yield tp, pp, ep
+
+
+def buffer_elems(spec: ModelSpec, lay: Layout, tp: int, pp: int, kind: int, dp: int = 0) -> int:
+    sv = stage_view(spec, lay, tp, pp, dp % lay.ep if kind >= EXPERT_PARAM else None)
+    return sv.n_pad if kind % 4 == 0 else sv.S
 
 
 # ------------------------------------------------------------------ flat access
@@ -379,27 +432,28 @@ def dict_reader(bufs: Dict[Tuple[int, int], np.ndarray]) -> Reader:
 def dp_pieces(sv: StageView, lay: Layout, lo: int, hi: int) -> List[Tuple[int, int, int, int]]:
     """Where flat elements [lo, hi) of a rank column live in the fp32 buffers (R6):
     [(dp rank, offset in that rank's buffer, flat offset, count)] in flat order.
-    Each bucket is cut into DP equal slices; a rank's buffer is the concatenation
-    of its slice of every bucket."""
-    out, prefix = [], 0
+    Each bucket is cut into equal slices, one per DP rank sharing the buffer
+    (sv.dp_ranks); a rank's buffer is the concatenation of its slice of every bucket."""
+    out, prefix, group = [], 0, sv.dp_ranks
     for b0, nb in sv.buckets:
-        sb = nb // lay.dp
-        for d in range(lay.dp):
-            a, b = max(lo, b0 + d * sb), min(hi, b0 + (d + 1) * sb)
+        sb = nb // len(group)
+        for j, d in enumerate(group):
+            a, b = max(lo, b0 + j * sb), min(hi, b0 + (j + 1) * sb)
             if a < b:
-                out.append((d, prefix + a - b0 - d * sb, a, b - a))
+                out.append((d, prefix + a - b0 - j * sb, a, b - a))
         prefix += sb
     return out
 
 
 def read_flat(read: Reader, lay: Layout, sv: StageView, tp: int, pp: int, kind: int, lo: int, hi: int,
-              dp_replica: int = 0) -> np.ndarray:
-    """Elements [lo, hi) of the (tp, pp) flat buffer of `kind`.
+              dp_replica: Optional[int] = None) -> np.ndarray:
+    """Elements [lo, hi) of the flat buffer `sv` of rank column (tp, pp), kind `kind`.
 
-    PARAM: taken from replica `dp_replica`.  fp32 kinds: concatenation of the
-    pieces held by the DP ranks (dp_pieces)."""
-    if kind == PARAM:
-        return np.asarray(read(lay.rank(tp, pp, dp_replica), kind, lo, hi))
+    bf16 kinds: taken from replica `dp_replica` (default: the first rank that holds
+    the buffer, R7).  fp32 kinds: concatenation of the pieces held by the DP ranks
+    (dp_pieces)."""
+    if kind % 4 == 0:
+        return np.asarray(read(lay.rank(tp, pp, sv.dp_ranks[0] if dp_replica is None else dp_replica), kind, lo, hi))
     parts = [np.asarray(read(lay.rank(tp, pp, d), kind, loc, loc + n)) for d, loc, _, n in dp_pieces(sv, lay, lo, hi)]
     return np.concatenate(parts) if parts else np.empty(0, WORD[kind])
 
@@ -415,20 +469,20 @@ def gather_logical(spec: ModelSpec, lay: Layout, kind: int, read: Reader,
     (Appendix A.2.1, Eq. 1: the shards of a configuration tile the tensor)."""
     shapes = logical_tensors(spec)
     want = set(shapes) if names is None else set(names)
-    logical = {n: np.zeros(shapes[n], WORD[kind]) for n in shapes if n in want}
+    mine = lambda n: (".x" in n) == (kind >= EXPERT_PARAM)   # expert tensors live in kinds 4..7, the others in 0..3
+    logical = {n: np.zeros(shapes[n], WORD[kind]) for n in shapes if n in want and mine(n)}
     hits = {n: np.zeros(shapes[n], np.uint8) for n in logical} if check else None
-    for pp in range(lay.pp):
-        for tp in range(lay.tp):
-            sv = stage_view(spec, lay, tp, pp)
-            for prm in sv.params:
-                if not prm.canonical or not any(b.name in want and b.canonical for b in prm.blocks):
-                    continue
-                local = read_flat(read, lay, sv, tp, pp, kind, prm.offset, prm.offset + prm.size).reshape(prm.shape)
-                for b in prm.blocks:
-                    if b.name in want and b.canonical:
-                        logical[b.name][b.idx] = local[b.loc]
-                        if hits is not None:
-                            hits[b.name][b.idx] += 1
+    for tp, pp, ep in columns(lay, kind):
+        sv = stage_view(spec, lay, tp, pp, ep)
+        for prm in sv.params:
+            if not prm.canonical or not any(b.name in logical and b.canonical for b in prm.blocks):
+                continue
+            local = read_flat(read, lay, sv, tp, pp, kind, prm.offset, prm.offset + prm.size).reshape(prm.shape)
+            for b in prm.blocks:
+                if b.name in logical and b.canonical:
+                    logical[b.name][b.idx] = local[b.loc]
+                    if hits is not None:
+                        hits[b.name][b.idx] += 1
     if hits is not None:
         for n, h in hits.items():
             if not (h == 1).all():
@@ -450,18 +504,18 @@ def split_logical(spec: ModelSpec, lay: Layout, kind: int,
                   logical: Dict[str, np.ndarray]) -> Dict[Tuple[int, int], np.ndarray]:
     """Every rank's buffer of `kind` for world `lay`; padding is +0 (R6)."""
     out: Dict[Tuple[int, int], np.ndarray] = {}
-    for pp in range(lay.pp):
-        for tp in range(lay.tp):
-            sv = stage_view(spec, lay, tp, pp)
-            flat = np.zeros(sv.n_pad, WORD[kind])
-            for prm in sv.params:
-                flat[prm.offset:prm.offset + prm.size] = build_shard(prm, logical, WORD[kind]).ravel()
-            for dp in range(lay.dp):
-                if kind == PARAM:
-                    out[(lay.rank(tp, pp, dp), kind)] = flat.copy()
-                else:                                # this rank's slice of every bucket, concatenated
-                    out[(lay.rank(tp, pp, dp), kind)] = np.concatenate(
-                        [flat[b0 + dp * (nb // lay.dp):b0 + (dp + 1) * (nb // lay.dp)] for b0, nb in sv.buckets])
+    for tp, pp, ep in columns(lay, kind):
+        sv = stage_view(spec, lay, tp, pp, ep)
+        flat = np.zeros(sv.n_pad, WORD[kind])
+        for prm in sv.params:
+            flat[prm.offset:prm.offset + prm.size] = build_shard(prm, logical, WORD[kind]).ravel()
+        n = len(sv.dp_ranks)
+        for j, dp in enumerate(sv.dp_ranks):
+            if kind % 4 == 0:
+                out[(lay.rank(tp, pp, dp), kind)] = flat.copy()
+            else:                                    # this rank's slice of every bucket, concatenated
+                out[(lay.rank(tp, pp, dp), kind)] = np.concatenate(
+                    [flat[b0 + j * (nb // n):b0 + (j + 1) * (nb // n)] for b0, nb in sv.buckets])
     return out
 
 
@@ -479,16 +533,16 @@ def rne_bf16(u: np.ndarray) -> np.ndarray:
 # ---------------------------------------------------------------------- reshard
 def reshard_state(spec: ModelSpec, src: Layout, dst: Layout,
                   src_bufs: Dict[Tuple[int, int], np.ndarray], derive_bf16: bool = False,
-                  kinds: Iterable[int] = KINDS) -> Dict[Tuple[int, int], np.ndarray]:
+                  kinds: Optional[Iterable[int]] = None) -> Dict[Tuple[int, int], np.ndarray]:
     """The whole result: gather under `src`, split under `dst`, kind by kind.
 
     derive_bf16: target PARAM is rne_bf16 of the gathered MASTER tensors (the
     element with the same logical index), not a copy of the source PARAM."""
     read = dict_reader(src_bufs)
     out: Dict[Tuple[int, int], np.ndarray] = {}
-    for kind in kinds:
-        if kind == PARAM and derive_bf16:
-            master = gather_logical(spec, src, MASTER, read)
+    for kind in (kinds_of(spec) if kinds is None else kinds):
+        if kind % 4 == 0 and derive_bf16:              # PARAM from MASTER, EXPERT_PARAM from EXPERT_MASTER
+            master = gather_logical(spec, src, kind + 1, read)
             logical = {n: rne_bf16(a) for n, a in master.items()}
         else:
             logical = gather_logical(spec, src, kind, read)
@@ -511,7 +565,8 @@ def expected_shards(spec: ModelSpec, lay: Layout, logical: Dict[str, np.ndarray]
                     yield tp, pp, sv, prm, build_shard(prm, logical, logical[prm.blocks[0].name].dtype)
 
 
-__all__ = ["PARAM", "MASTER", "ADAM_M", "ADAM_V", "KINDS", "WORD", "ModelSpec", "Layout",
+__all__ = ["PARAM", "MASTER", "ADAM_M", "ADAM_V", "KINDS", "EXPERT_PARAM", "EXPERT_MASTER", "EXPERT_ADAM_M",
+           "EXPERT_ADAM_V", "EXPERT_KINDS", "kinds_of", "columns", "WORD", "ModelSpec", "Layout",
            "check_supported", "padded_vocab", "logical_tensors", "Block", "PhysParam", "StageView", "stage_layers", "stage_view",
            "buffer_elems", "Reader", "dict_reader", "dp_pieces", "read_flat", "gather_logical", "build_shard",
            "split_logical", "rne_bf16", "reshard_state", "expected_shards"]

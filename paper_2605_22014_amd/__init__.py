@@ -4,7 +4,7 @@ Thin Python binding over libliver.so (argument marshalling only; every step of
 the path runs in the library's HIP kernels).  Importing this package fails
 loudly if the library has not been built: there is no fallback path.
 """
-from ._binding import (ADAM_M, ADAM_V, MASTER, PARAM, LiverError, Layout, ModelSpec, Plan, PlanInfo, Desc,
+from ._binding import (ADAM_M, ADAM_V, MASTER, PARAM, EXPERT_PARAM, EXPERT_MASTER, EXPERT_ADAM_M, EXPERT_ADAM_V, NUM_KINDS, LiverError, Layout, ModelSpec, Plan, PlanInfo, Desc,
                        LIST_DIRECT, LIST_PACK, LIST_UNPACK, OP_COPY, OP_CAST_BF16, OP_ZERO,
                        liver_pack, liver_plan_buffer_bytes, liver_plan_buffer_used, liver_plan_create,
                        liver_plan_desc, liver_plan_desc_count, liver_plan_destroy, liver_plan_info,

@@ -41,12 +41,12 @@ class LiverError(RuntimeError):
 
 class _Spec(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "ffn", "vocab", "max_pos")] \
-        + [("flags", C.c_uint32)]
+        + [("flags", C.c_uint32), ("n_experts", C.c_int32)]
 
 
 class _Layout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("tp", "pp", "dp", "pad_multiple", "only_tp", "only_pp", "only_dp")] \
-        + [("flags", C.c_uint32), ("kind_mask", C.c_uint32), ("vpp", C.c_int32), ("vocab_multiple", C.c_int32), ("pp_first", C.c_int32), ("pp_last", C.c_int32), ("bucket_elems", C.c_int64)]
+        + [("flags", C.c_uint32), ("kind_mask", C.c_uint32), ("vpp", C.c_int32), ("vocab_multiple", C.c_int32), ("pp_first", C.c_int32), ("pp_last", C.c_int32), ("bucket_elems", C.c_int64), ("ep", C.c_int32)]
 
 
 class PlanInfo(C.Structure):
@@ -74,12 +74,13 @@ class ModelSpec:
     norm_bias: bool = False
     linear_bias: bool = False
     tied_embed: bool = False
+    n_experts: int = 0          # > 0: mixture of experts (router in the dense buffers, experts in kinds 4..7)
 
     def _c(self) -> _Spec:
         flags = (_GLU * self.glu) | (_NORM_BIAS * self.norm_bias) | (_LINEAR_BIAS * self.linear_bias) \
             | (_TIED * self.tied_embed)
         return _Spec(self.n_layers, self.hidden, self.n_q_heads, self.n_kv_heads, self.ffn, self.vocab,
-                     self.max_pos, flags)
+                     self.max_pos, flags, self.n_experts)
 
 
 @dataclass(frozen=True)
@@ -98,6 +99,7 @@ class Layout:
     pp_first: int = 0                            # layers on the first / last stage (0 = even split)
     pp_last: int = 0
     bucket_elems: int = 0                        # flat buffer cut into buckets of >= this many elements (0 = one)
+    ep: int = 1                                  # expert-parallel size (divides dp and n_experts)
 
     @property
     def n_ranks(self) -> int:
@@ -109,7 +111,7 @@ class Layout:
     def _c(self) -> _Layout:
         mask = 0 if self.kinds is None else sum(1 << k for k in set(self.kinds))
         return _Layout(self.tp, self.pp, self.dp, self.pad_multiple, self.only_tp, self.only_pp, self.only_dp,
-                       _DERIVE * self.derive_bf16, mask, self.vpp, self.vocab_multiple, self.pp_first, self.pp_last, self.bucket_elems)
+                       _DERIVE * self.derive_bf16, mask, self.vpp, self.vocab_multiple, self.pp_first, self.pp_last, self.bucket_elems, self.ep)
 
 
 def _load() -> C.CDLL:

@@ -144,12 +144,15 @@ int liver_plan_buffer_bytes(const liver_plan_t* plan, int side, int rank, int ki
     const liver_layout_t& lay = side ? plan->dst : plan->src;
     if (rank < 0 || rank >= n_ranks(lay)) return fail(LIVER_E_INVALID_ARG, "rank out of range");
     const int pp = rank / (lay.tp * lay.dp);
-    const liver::StageSize& st = (side ? plan->dst_stage : plan->src_stage)[pp];
-    if (kind >= LIVER_EXPERT_PARAM_BF16) {  // expert buffers exist only for mixture-of-experts models
+    const bool expert = kind >= LIVER_EXPERT_PARAM_BF16;
+    const std::vector<liver::StageSize>& stages = side ? (expert ? plan->dst_xstage : plan->dst_stage)
+                                                       : (expert ? plan->src_xstage : plan->src_stage);
+    if (stages.empty()) {  // expert buffers exist only for mixture-of-experts models
         *out = 0;
         return LIVER_OK;
     }
-    *out = kind == LIVER_PARAM_BF16 ? (size_t)st.n_pad * 2 : (size_t)st.S * 4;
+    const liver::StageSize& st = stages[pp];
+    *out = kind % 4 == 0 ? (size_t)st.n_pad * 2 : (size_t)st.S * 4;
     return LIVER_OK;
 }
 

@@ -14,8 +14,10 @@ namespace {
 size_t buffer_bytes(const liver_plan* plan, const liver::BufRef& r) {
     if (r.side == 2) return plan->chunk_bytes;
     const liver_layout_t& lay = r.side ? plan->dst : plan->src;
-    const liver::StageSize& st = (r.side ? plan->dst_stage : plan->src_stage)[r.rank / (lay.tp * lay.dp)];
-    return r.kind == LIVER_PARAM_BF16 ? (size_t)st.n_pad * 2 : (size_t)st.S * 4;
+    const bool expert = r.kind >= LIVER_EXPERT_PARAM_BF16;
+    const liver::StageSize& st = (r.side ? (expert ? plan->dst_xstage : plan->dst_stage)
+                                         : (expert ? plan->src_xstage : plan->src_stage))[r.rank / (lay.tp * lay.dp)];
+    return r.kind % 4 == 0 ? (size_t)st.n_pad * 2 : (size_t)st.S * 4;
 }
 
 uint32_t bf16_rne(uint32_t u) {

@@ -88,7 +88,8 @@ struct liver_plan {
     liver_model_spec_t spec{};
     liver_layout_t src{}, dst{};
     size_t chunk_bytes = 0;
-    std::vector<liver::StageSize> src_stage, dst_stage;  // per pp
+    std::vector<liver::StageSize> src_stage, dst_stage;  // per pp: the dense buffers (kinds 0..3)
+    std::vector<liver::StageSize> src_xstage, dst_xstage;  // per pp: the expert buffers (kinds 4..7); empty if dense
     liver::List direct, pack, unpack;
     liver_plan_info_t info{};
     std::vector<uint8_t> used[2];  // [side][rank*LIVER_NUM_KINDS+kind]

@@ -24,14 +24,16 @@ namespace {
 using i64 = int64_t;
 
 struct Geo {
-    i64 L, H, hd, nq, nkv, qpg, Q, KV, F, V, P;
+    i64 L, H, hd, nq, nkv, qpg, Q, KV, F, V, P, E;  // E: experts per layer (0 = dense model)
     bool glu, norm_bias, lin_bias, tied;
 };
 
 // logical tensor ids
 enum { T_EMBED_WORD = 0, T_EMBED_POS, T_FINAL_W, T_FINAL_B, T_LM_HEAD, T_GLOBALS };
 enum { LN1_W = 0, LN1_B, Q_W, K_W, V_W, Q_B, K_B, V_B, O_W, O_B, LN2_W, LN2_B, GATE_W, UP_W, GATE_B, UP_B,
-       DOWN_W, DOWN_B, T_PER_LAYER };
+       DOWN_W, DOWN_B, ROUTER_W, T_PER_LAYER };
+// expert tensors follow all dense ones: id = T_GLOBALS + L*T_PER_LAYER + (l*E + e)*X_PER_EXPERT + leaf
+enum { X_GATE_W = 0, X_UP_W, X_GATE_B, X_UP_B, X_DOWN_W, X_DOWN_B, X_PER_EXPERT };
 
 // A rectangle of logical tensor `tensor` held densely (row-major, row length
 // c1-c0) at element offset `loff` of a rank column's flat buffer.
@@ -82,14 +84,18 @@ std::vector<i64> stage_layers(i64 L, const liver_layout_t& lay, int pp) {
     return out;
 }
 
-Column build_column(const Geo& g, const liver_layout_t& lay, int tp, int pp) {
+inline int ep_of(const liver_layout_t& l) { return l.ep > 1 ? l.ep : 1; }
+
+// ep < 0: the dense buffer of rank column (tp, pp).  ep >= 0: the expert buffer held by the ranks of
+// expert-parallel index ep (mixture-of-experts models only).
+Column build_column(const Geo& g, const liver_layout_t& lay, int tp, int pp, int ep = -1) {
     const int TP = lay.tp, PP = lay.pp;
     const i64 vocab_multiple = lay.vocab_multiple;
     Column col;
     col.tp = tp;
     col.pp = pp;
     i64 off = 0, bucket_start = 0, params_in_bucket = 0;
-    const i64 quantum = (i64)lay.dp * lay.pad_multiple;
+    const i64 quantum = (i64)(ep < 0 ? lay.dp : lay.dp / ep_of(lay)) * lay.pad_multiple;  // ranks sharing the buffer
     // A bucket is zero-padded to a multiple of DP*pad_multiple elements when it closes.
     auto close_bucket = [&]() {
         const i64 used = off - bucket_start, padded = (used + quantum - 1) / quantum * quantum;
@@ -124,6 +130,28 @@ Column build_column(const Geo& g, const liver_layout_t& lay, int tp, int pp) {
         col.last_slot = slot;
         end_param();
     };
+    // fc1 (+bias), fc2 (+bias) of one FFN: tensor ids gate_w.. given by the caller
+    auto add_ffn = [&](int slot, int gate_w, int up_w, int gate_b, int up_b, int down_w, int down_b) {
+        if (g.glu) add(gate_w, slot, tp * fn, (tp + 1) * fn, 0, g.H, true, false);
+        add(up_w, slot, tp * fn, (tp + 1) * fn, 0, g.H, true);
+        if (g.lin_bias) {
+            if (g.glu) add(gate_b, slot, 0, 1, tp * fn, (tp + 1) * fn, true, false);
+            add(up_b, slot, 0, 1, tp * fn, (tp + 1) * fn, true);
+        }
+        add(down_w, slot, 0, g.H, tp * fn, (tp + 1) * fn, true);  // row-parallel
+        if (g.lin_bias) add(down_b, slot, 0, 1, 0, g.H, lead);
+    };
+    if (ep >= 0) {  // expert buffer: layer by layer, expert by expert
+        const i64 per = g.E / ep_of(lay);
+        for (const i64 l : stage_layers(g.L, lay, pp))
+            for (i64 e = ep * per; e < (ep + 1) * per; ++e) {
+                const int x = T_GLOBALS + (int)g.L * T_PER_LAYER + (int)(l * g.E + e) * X_PER_EXPERT;
+                add_ffn(1 + (int)l, x + X_GATE_W, x + X_UP_W, x + X_GATE_B, x + X_UP_B, x + X_DOWN_W, x + X_DOWN_B);
+            }
+        if (params_in_bucket > 0 || col.buckets.empty()) close_bucket();
+        col.n_pad = off;
+        return col;
+    }
     if (pp == 0) {
         add_vocab(T_EMBED_WORD, 0, true);
         if (g.P) add(T_EMBED_POS, 0, 0, g.P, 0, g.H, lead);
@@ -164,14 +192,10 @@ Column build_column(const Geo& g, const liver_layout_t& lay, int tp, int pp) {
         if (g.lin_bias) add(b + O_B, slot, 0, 1, 0, g.H, lead);
         add(b + LN2_W, slot, 0, 1, 0, g.H, lead);
         if (g.norm_bias) add(b + LN2_B, slot, 0, 1, 0, g.H, lead);
-        if (g.glu) add(b + GATE_W, slot, tp * fn, (tp + 1) * fn, 0, g.H, true, false);
-        add(b + UP_W, slot, tp * fn, (tp + 1) * fn, 0, g.H, true);
-        if (g.lin_bias) {
-            if (g.glu) add(b + GATE_B, slot, 0, 1, tp * fn, (tp + 1) * fn, true, false);
-            add(b + UP_B, slot, 0, 1, tp * fn, (tp + 1) * fn, true);
-        }
-        add(b + DOWN_W, slot, 0, g.H, tp * fn, (tp + 1) * fn, true);
-        if (g.lin_bias) add(b + DOWN_B, slot, 0, 1, 0, g.H, lead);
+        if (g.E > 0)
+            add(b + ROUTER_W, slot, 0, g.E, 0, g.H, lead);  // the experts themselves live in the expert buffers
+        else
+            add_ffn(slot, b + GATE_W, b + UP_W, b + GATE_B, b + UP_B, b + DOWN_W, b + DOWN_B);
     }
     if (pp == PP - 1) {
         const int slot = (int)g.L + 1;
@@ -199,7 +223,7 @@ struct Entry {
     std::vector<Dst> dsts;
 };
 
-inline int elem_bytes(int kind) { return kind == LIVER_PARAM_BF16 ? 2 : 4; }
+inline int elem_bytes(int kind) { return kind % 4 == 0 ? 2 : 4; }  // kinds 0 and 4 are bf16
 
 // Payload elements [p0, p1) of `e` (row-major over rows x run) as up to three
 // pieces: the tail of a row, whole rows, the head of a row.
@@ -288,7 +312,18 @@ struct Builder {
         const int tp = rank % S.tp, dp = (rank / S.tp) % S.dp, pp = rank / (S.tp * S.dp);
         return (S.only_tp < 0 || S.only_tp == tp) && (S.only_pp < 0 || S.only_pp == pp) && (S.only_dp < 0 || S.only_dp == dp);
     }
-    bool kind_on(int k) const { return plan.dst.kind_mask == 0 || ((plan.dst.kind_mask >> k) & 1u); }
+    bool kind_on(int k) const { return plan.dst.kind_mask == 0 || ((plan.dst.kind_mask >> (k % 4)) & 1u); }
+
+    // The family being planned: the dense buffers (kinds 0..3, shared by all DP ranks of a column) or the
+    // expert buffers (kinds 4..7, shared by the DP ranks with the same expert-parallel index).
+    bool expert = false;
+    int kbase() const { return expert ? LIVER_EXPERT_PARAM_BF16 : LIVER_PARAM_BF16; }
+    const std::vector<StageSize>& stages(bool dst) const {
+        return dst ? (expert ? plan.dst_xstage : plan.dst_stage) : (expert ? plan.src_xstage : plan.src_stage);
+    }
+    int group_size(const liver_layout_t& l) const { return expert ? l.dp / ep_of(l) : l.dp; }
+    // j-th rank (in slice order) of the group that shares the buffer of expert-parallel index ep
+    int group_dp(const liver_layout_t& l, int ep, int j) const { return expert ? ep + ep_of(l) * j : j; }
 
     void push_bounded(Entry&& e) {  // keep every entry below 2^30 elements (32-bit unit counters)
         const i64 lim = i64(1) << 30, total = e.rows * e.run;
@@ -301,26 +336,28 @@ struct Builder {
 
     // One intersection piece in flat coordinates of columns (s_tp,s_pp) -> (d_tp,d_pp):
     // expand it per buffer kind, clipping the fp32 kinds at the DP slice boundaries.
-    void expand(int slot, int s_tp, int s_pp, int d_tp, int d_pp, i64 s_off, i64 s_stride, i64 d_off,
-                i64 d_stride, i64 rows, i64 run) {
+    void expand(int slot, int s_tp, int s_pp, int s_ep, int d_tp, int d_pp, int d_ep, i64 s_off, i64 s_stride,
+                i64 d_off, i64 d_stride, i64 rows, i64 run) {
         const liver_layout_t &S = plan.src, &D = plan.dst;
         const bool derive = (D.flags & LIVER_DERIVE_BF16) != 0;
+        const int kb = kbase(), n_dst = group_size(D);
         if (kind_on(LIVER_PARAM_BF16) && !derive) {
-            for (int dp = 0; dp < D.dp; ++dp) {
+            for (int j = 0; j < n_dst; ++j) {
+                const int dp = group_dp(D, d_ep, j);
                 if (!dst_dp_planned(dp)) continue;
                 Entry e;
                 e.slot = slot;
-                e.src_rank = rank_of(S, s_tp, s_pp, 0);  // replicas are identical: read dp 0
-                e.src_kind = LIVER_PARAM_BF16;
+                e.src_rank = rank_of(S, s_tp, s_pp, group_dp(S, s_ep, 0));  // replicas are identical: read the first
+                e.src_kind = kb;
                 e.src_off = s_off, e.src_stride = s_stride, e.rows = rows, e.run = run;
-                e.dsts.push_back({rank_of(D, d_tp, d_pp, dp), LIVER_PARAM_BF16, LIVER_OP_COPY, d_off, d_stride});
+                e.dsts.push_back({rank_of(D, d_tp, d_pp, dp), kb, LIVER_OP_COPY, d_off, d_stride});
                 push_bounded(std::move(e));
             }
         }
         const bool any_f32 = kind_on(LIVER_MASTER_F32) || kind_on(LIVER_ADAM_M_F32) || kind_on(LIVER_ADAM_V_F32);
         if (!any_f32 && !(derive && kind_on(LIVER_PARAM_BF16))) return;
         // cut where the owning bucket / DP rank changes, on the source and on the target side
-        const StageSize &sst = plan.src_stage[s_pp], &dst_st = plan.dst_stage[d_pp];
+        const StageSize &sst = stages(false)[s_pp], &dst_st = stages(true)[d_pp];
         std::vector<i64> cuts{0, rows * run};
         boundary_cuts(s_off, s_stride, rows, run, sst.bounds, cuts);
         boundary_cuts(d_off, d_stride, rows, run, dst_st.bounds, cuts);
@@ -334,39 +371,44 @@ struct Builder {
         std::vector<Entry> parts;
         for (size_t c = 0; c + 1 < cuts.size(); ++c) slice(flat, cuts[c], cuts[c + 1], parts);
         for (const Entry& p : parts) {
-            int sdp, ddp;
+            int sj, dj;  // position of the owning rank inside its group
             i64 s_local, d_local;
-            locate(sst, p.src_off, sdp, s_local);
-            locate(dst_st, p.dsts[0].off, ddp, d_local);
+            locate(sst, p.src_off, sj, s_local);
+            locate(dst_st, p.dsts[0].off, dj, d_local);
+            const int sdp = group_dp(S, s_ep, sj), ddp = group_dp(D, d_ep, dj);
             for (int k = LIVER_MASTER_F32; k <= LIVER_ADAM_V_F32; ++k) {
                 Entry e;
                 e.slot = slot;
                 e.src_rank = rank_of(S, s_tp, s_pp, sdp);
-                e.src_kind = k;
+                e.src_kind = kb + k;
                 e.src_off = s_local, e.src_stride = p.src_stride, e.rows = p.rows, e.run = p.run;
                 if (kind_on(k) && dst_dp_planned(ddp))
-                    e.dsts.push_back({rank_of(D, d_tp, d_pp, ddp), k, LIVER_OP_COPY, d_local, p.dsts[0].stride});
+                    e.dsts.push_back({rank_of(D, d_tp, d_pp, ddp), kb + k, LIVER_OP_COPY, d_local, p.dsts[0].stride});
                 if (k == LIVER_MASTER_F32 && derive && kind_on(LIVER_PARAM_BF16))
-                    for (int dp = 0; dp < D.dp; ++dp)  // PARAM replicas come from the MASTER element
-                        if (dst_dp_planned(dp))        // with the same logical index
-                            e.dsts.push_back({rank_of(D, d_tp, d_pp, dp), LIVER_PARAM_BF16, LIVER_OP_CAST_BF16,
-                                              p.dsts[0].off, p.dsts[0].stride});
+                    for (int j = 0; j < n_dst; ++j) {  // bf16 replicas come from the MASTER element
+                        const int dp = group_dp(D, d_ep, j);  // with the same logical index
+                        if (dst_dp_planned(dp))
+                            e.dsts.push_back({rank_of(D, d_tp, d_pp, dp), kb, LIVER_OP_CAST_BF16, p.dsts[0].off,
+                                              p.dsts[0].stride});
+                    }
                 if (!e.dsts.empty()) push_bounded(std::move(e));
             }
         }
     }
 
-    void zero_padding(const Column& col) {
+    void zero_padding(const Column& col, int d_ep) {
         const liver_layout_t& D = plan.dst;
-        const StageSize& st = plan.dst_stage[col.pp];
+        const StageSize& st = stages(true)[col.pp];
+        const int kb = kbase();
         for (const ZeroRegion& z : col.zeros) {  // vocabulary padding rows and the padding of every bucket
             if (kind_on(LIVER_PARAM_BF16))
-                for (int dp = 0; dp < D.dp; ++dp) {
+                for (int j = 0; j < group_size(D); ++j) {
+                    const int dp = group_dp(D, d_ep, j);
                     if (!dst_dp_planned(dp)) continue;
                     Entry e;
                     e.slot = z.slot;
                     e.run = z.n;
-                    e.dsts.push_back({rank_of(D, col.tp, col.pp, dp), LIVER_PARAM_BF16, LIVER_OP_ZERO, z.off, z.n});
+                    e.dsts.push_back({rank_of(D, col.tp, col.pp, dp), kb, LIVER_OP_ZERO, z.off, z.n});
                     push_bounded(std::move(e));
                 }
             // fp32 kinds: the region may span several DP ranks' slices
@@ -375,16 +417,17 @@ struct Builder {
                 cuts.push_back(*it);
             std::sort(cuts.begin(), cuts.end());
             for (size_t c = 0; c + 1 < cuts.size(); ++c) {
-                int dp;
+                int j;
                 i64 local;
-                locate(st, cuts[c], dp, local);
+                locate(st, cuts[c], j, local);
+                const int dp = group_dp(D, d_ep, j);
                 if (!dst_dp_planned(dp)) continue;
                 for (int k = LIVER_MASTER_F32; k <= LIVER_ADAM_V_F32; ++k) {
                     if (!kind_on(k)) continue;
                     Entry e;
                     e.slot = z.slot;
                     e.run = cuts[c + 1] - cuts[c];
-                    e.dsts.push_back({rank_of(D, col.tp, col.pp, dp), k, LIVER_OP_ZERO, local, e.run});
+                    e.dsts.push_back({rank_of(D, col.tp, col.pp, dp), kb + k, LIVER_OP_ZERO, local, e.run});
                     push_bounded(std::move(e));
                 }
             }
@@ -392,6 +435,7 @@ struct Builder {
     }
 
     int run();
+    int plan_family();
     void emit_lists();
     int lower(List& list, bool staged);
 };
@@ -400,14 +444,14 @@ int Builder::run() {
     const liver_model_spec_t& sp = plan.spec;
     const liver_layout_t &S = plan.src, &D = plan.dst;
     if (sp.n_layers <= 0 || sp.hidden <= 0 || sp.n_q_heads <= 0 || sp.n_kv_heads <= 0 || sp.ffn <= 0 ||
-        sp.vocab <= 0 || sp.max_pos < 0 || (sp.flags & ~15u)) {
+        sp.vocab <= 0 || sp.max_pos < 0 || (sp.flags & ~15u) || sp.n_experts < 0) {
         why = "model_spec: dimensions must be positive";
         return LIVER_E_INVALID_ARG;
     }
     for (const liver_layout_t* l : {&S, &D})
         if (l->tp <= 0 || l->pp <= 0 || l->dp <= 0 || l->pad_multiple <= 0 || l->vpp < 0 || l->vocab_multiple < 0 ||
-            l->pp_first < 0 || l->pp_last < 0 || l->bucket_elems < 0) {
-            why = "layout: tp, pp, dp, pad_multiple must be positive; vpp, vocab_multiple, pp_first, pp_last, bucket_elems non-negative";
+            l->pp_first < 0 || l->pp_last < 0 || l->bucket_elems < 0 || l->ep < 0) {
+            why = "layout: tp, pp, dp, pad_multiple must be positive; vpp, vocab_multiple, pp_first, pp_last, bucket_elems, ep non-negative";
             return LIVER_E_INVALID_ARG;
         }
     if (plan.chunk_bytes < 256 || plan.chunk_bytes % 256) {
@@ -423,8 +467,9 @@ int Builder::run() {
                            (l->tp % sp.n_kv_heads == 0 && (sp.n_q_heads / sp.n_kv_heads) % (l->tp / sp.n_kv_heads) == 0);
         bool stages_ok = true;
         for (int p = 0; p < l->pp; ++p) stages_ok = stages_ok && !stage_layers(sp.n_layers, *l, p).empty();
-        if (!stages_ok || !kv_ok || sp.ffn % l->tp || (sp.vocab % l->tp && l->vocab_multiple == 0)) {
-            why = "layers do not split over the stages, ffn % tp or vocab % tp != 0, or kv heads neither split nor replicated evenly over tp";
+        const bool ep_ok = sp.n_experts > 0 ? (l->dp % ep_of(*l) == 0 && sp.n_experts % ep_of(*l) == 0) : ep_of(*l) == 1;
+        if (!stages_ok || !kv_ok || !ep_ok || sp.ffn % l->tp || (sp.vocab % l->tp && l->vocab_multiple == 0)) {
+            why = "layers do not split over the stages, ffn % tp or vocab % tp != 0, kv heads neither split nor replicated evenly over tp, or ep does not divide dp and n_experts";
             return LIVER_E_UNSUPPORTED;
         }
     }
@@ -444,104 +489,39 @@ int Builder::run() {
     }
     g.L = sp.n_layers, g.H = sp.hidden, g.nq = sp.n_q_heads, g.nkv = sp.n_kv_heads;
     g.hd = g.H / g.nq, g.qpg = g.nq / g.nkv, g.Q = g.nq * g.hd, g.KV = g.nkv * g.hd;
-    g.F = sp.ffn, g.V = sp.vocab, g.P = sp.max_pos;
+    g.F = sp.ffn, g.V = sp.vocab, g.P = sp.max_pos, g.E = sp.n_experts;
     g.glu = sp.flags & LIVER_GLU, g.norm_bias = sp.flags & LIVER_NORM_BIAS;
     g.lin_bias = sp.flags & LIVER_LINEAR_BIAS, g.tied = sp.flags & LIVER_TIED_EMBED;
 
     // --- views of both worlds (Abstract Resource View) ---------------------------------
-    auto stage_sizes = [&](const liver_layout_t& lay, std::vector<StageSize>& out) {
+    auto stage_sizes = [&](const liver_layout_t& lay, std::vector<StageSize>& out, bool xp) {
         out.resize(lay.pp);
+        const int group = xp ? lay.dp / ep_of(lay) : lay.dp;
         for (int pp = 0; pp < lay.pp; ++pp) {
-            const Column c = build_column(g, lay, 0, pp);
+            const Column c = build_column(g, lay, 0, pp, xp ? 0 : -1);  // sizes do not depend on tp / ep
             StageSize s;
-            s.n_local = c.n_local, s.n_pad = c.n_pad, s.S = c.n_pad / lay.dp;
+            s.n_local = c.n_local, s.n_pad = c.n_pad, s.S = c.n_pad / group;
             i64 prefix = 0;
             for (const auto& b : c.buckets) {
                 Bucket k;
-                k.start = b.first, k.padded = b.second, k.slice = b.second / lay.dp, k.prefix = prefix;
+                k.start = b.first, k.padded = b.second, k.slice = b.second / group, k.prefix = prefix;
                 prefix += k.slice;
-                for (int d = 0; d < lay.dp; ++d) s.bounds.push_back(k.start + d * k.slice);
+                for (int d = 0; d < group; ++d) s.bounds.push_back(k.start + d * k.slice);
                 s.buckets.push_back(k);
             }
             out[pp] = s;
         }
     };
-    stage_sizes(S, plan.src_stage);
-    stage_sizes(D, plan.dst_stage);
-
-    const int n_tensors = T_GLOBALS + (int)g.L * T_PER_LAYER;
-    struct SrcRect {
-        Rect r;
-        int tp, pp;
-    };
-    std::vector<std::vector<SrcRect>> by_tensor(n_tensors);  // pruning: only views of the same tensor meet
-    for (int pp = 0; pp < S.pp; ++pp)
-        for (int tp = 0; tp < S.tp; ++tp) {
-            Column c = build_column(g, S, tp, pp);
-            for (const Rect& r : c.rects)
-                if (r.canonical) by_tensor[r.tensor].push_back({r, tp, pp});
-        }
-
-    // --- intersect every target view with the source views of its tensor ----------------
-    struct Piece {
-        int slot, s_tp, s_pp;
-        i64 s_off, s_stride, d_off, d_stride, rows, run;
-    };
-    for (int pp = 0; pp < D.pp; ++pp) {
-        if (D.only_pp >= 0 && D.only_pp != pp) continue;
-        for (int tp = 0; tp < D.tp; ++tp) {
-            if (D.only_tp >= 0 && D.only_tp != tp) continue;
-            Column col = build_column(g, D, tp, pp);
-            std::vector<Piece> pieces;
-            for (const Rect& d : col.rects) {
-                const i64 dw = d.c1 - d.c0;
-                i64 covered = 0;
-                for (const SrcRect& sr : by_tensor[d.tensor]) {
-                    const Rect& s = sr.r;
-                    const i64 r0 = std::max(d.r0, s.r0), r1 = std::min(d.r1, s.r1);
-                    const i64 c0 = std::max(d.c0, s.c0), c1 = std::min(d.c1, s.c1);
-                    if (r0 >= r1 || c0 >= c1) continue;  // empty intersection: no task
-                    const i64 sw = s.c1 - s.c0;
-                    Piece p{d.slot, sr.tp, sr.pp, s.loff + (r0 - s.r0) * sw + (c0 - s.c0), sw,
-                            d.loff + (r0 - d.r0) * dw + (c0 - d.c0), dw, r1 - r0, c1 - c0};
-                    if (p.rows == 1 || (p.s_stride == p.run && p.d_stride == p.run)) {
-                        p.run *= p.rows;  // dense on both sides: one run
-                        p.rows = 1;
-                        p.s_stride = p.d_stride = p.run;
-                    }
-                    covered += p.rows * p.run;
-                    pieces.push_back(p);
-                }
-                if (covered != (d.r1 - d.r0) * dw) {  // Eq. 1 would be violated
-                    why = "internal: a target view is not tiled by the source views";
-                    return LIVER_E_UNSUPPORTED;
-                }
-            }
-            // merge pieces that continue each other on both sides (same source column)
-            std::sort(pieces.begin(), pieces.end(), [](const Piece& a, const Piece& b) { return a.d_off < b.d_off; });
-            std::vector<Piece> merged;
-            for (const Piece& p : pieces) {
-                if (!merged.empty()) {
-                    Piece& m = merged.back();
-                    const bool same = m.slot == p.slot && m.s_tp == p.s_tp && m.s_pp == p.s_pp;
-                    if (same && m.rows == 1 && p.rows == 1 && p.s_off == m.s_off + m.run && p.d_off == m.d_off + m.run) {
-                        m.run += p.run;
-                        m.s_stride = m.d_stride = m.run;
-                        continue;
-                    }
-                    if (same && m.rows > 1 && p.rows > 1 && m.run == p.run && m.s_stride == p.s_stride &&
-                        m.d_stride == p.d_stride && p.s_off == m.s_off + m.rows * m.s_stride &&
-                        p.d_off == m.d_off + m.rows * m.d_stride) {
-                        m.rows += p.rows;
-                        continue;
-                    }
-                }
-                merged.push_back(p);
-            }
-            for (const Piece& p : merged)
-                expand(p.slot, p.s_tp, p.s_pp, tp, pp, p.s_off, p.s_stride, p.d_off, p.d_stride, p.rows, p.run);
-            zero_padding(col);
-        }
+    stage_sizes(S, plan.src_stage, false);
+    stage_sizes(D, plan.dst_stage, false);
+    if (g.E > 0) {
+        stage_sizes(S, plan.src_xstage, true);
+        stage_sizes(D, plan.dst_xstage, true);
+    }
+    for (int fam = 0; fam < (g.E > 0 ? 2 : 1); ++fam) {  // dense buffers, then expert buffers
+        expert = fam == 1;
+        const int rc = plan_family();
+        if (rc != LIVER_OK) return rc;
     }
     // --- stream order: layer-major, then target rank, kind, target offset ---------------
     std::stable_sort(entries.begin(), entries.end(), [](const Entry& a, const Entry& b) {
@@ -579,6 +559,90 @@ int Builder::run() {
     plan.pack.dev_offset = nd * sizeof(DevDesc);
     plan.unpack.dev_offset = (nd + np) * sizeof(DevDesc);
     info.table_bytes_device = (i64)((nd + np + nu) * sizeof(DevDesc));
+    return LIVER_OK;
+}
+
+// Views, intersections and entries of one buffer family (`expert` selects it).
+int Builder::plan_family() {
+    const liver_layout_t &S = plan.src, &D = plan.dst;
+    const int n_tensors = T_GLOBALS + (int)g.L * T_PER_LAYER + (int)(g.L * g.E) * X_PER_EXPERT;
+    const int s_eps = expert ? ep_of(S) : 1, d_eps = expert ? ep_of(D) : 1;
+    struct SrcRect {
+        Rect r;
+        int tp, pp, ep;
+    };
+    std::vector<std::vector<SrcRect>> by_tensor(n_tensors);  // pruning: only views of the same tensor meet
+    for (int pp = 0; pp < S.pp; ++pp)
+        for (int tp = 0; tp < S.tp; ++tp)
+            for (int ep = 0; ep < s_eps; ++ep) {
+                Column c = build_column(g, S, tp, pp, expert ? ep : -1);
+                for (const Rect& r : c.rects)
+                    if (r.canonical) by_tensor[r.tensor].push_back({r, tp, pp, ep});
+            }
+
+    // --- intersect every target view with the source views of its tensor ----------------
+    struct Piece {
+        int slot, s_tp, s_pp, s_ep;
+        i64 s_off, s_stride, d_off, d_stride, rows, run;
+    };
+    for (int pp = 0; pp < D.pp; ++pp) {
+        if (D.only_pp >= 0 && D.only_pp != pp) continue;
+        for (int tp = 0; tp < D.tp; ++tp)
+          for (int d_ep = 0; d_ep < d_eps; ++d_ep) {
+            if (D.only_tp >= 0 && D.only_tp != tp) continue;
+            if (expert && D.only_dp >= 0 && D.only_dp % ep_of(D) != d_ep) continue;  // that rank holds other experts
+            Column col = build_column(g, D, tp, pp, expert ? d_ep : -1);
+            std::vector<Piece> pieces;
+            for (const Rect& d : col.rects) {
+                const i64 dw = d.c1 - d.c0;
+                i64 covered = 0;
+                for (const SrcRect& sr : by_tensor[d.tensor]) {
+                    const Rect& s = sr.r;
+                    const i64 r0 = std::max(d.r0, s.r0), r1 = std::min(d.r1, s.r1);
+                    const i64 c0 = std::max(d.c0, s.c0), c1 = std::min(d.c1, s.c1);
+                    if (r0 >= r1 || c0 >= c1) continue;  // empty intersection: no task
+                    const i64 sw = s.c1 - s.c0;
+                    Piece p{d.slot, sr.tp, sr.pp, sr.ep, s.loff + (r0 - s.r0) * sw + (c0 - s.c0), sw,
+                            d.loff + (r0 - d.r0) * dw + (c0 - d.c0), dw, r1 - r0, c1 - c0};
+                    if (p.rows == 1 || (p.s_stride == p.run && p.d_stride == p.run)) {
+                        p.run *= p.rows;  // dense on both sides: one run
+                        p.rows = 1;
+                        p.s_stride = p.d_stride = p.run;
+                    }
+                    covered += p.rows * p.run;
+                    pieces.push_back(p);
+                }
+                if (covered != (d.r1 - d.r0) * dw) {  // Eq. 1 would be violated
+                    why = "internal: a target view is not tiled by the source views";
+                    return LIVER_E_UNSUPPORTED;
+                }
+            }
+            // merge pieces that continue each other on both sides (same source column)
+            std::sort(pieces.begin(), pieces.end(), [](const Piece& a, const Piece& b) { return a.d_off < b.d_off; });
+            std::vector<Piece> merged;
+            for (const Piece& p : pieces) {
+                if (!merged.empty()) {
+                    Piece& m = merged.back();
+                    const bool same = m.slot == p.slot && m.s_tp == p.s_tp && m.s_pp == p.s_pp && m.s_ep == p.s_ep;
+                    if (same && m.rows == 1 && p.rows == 1 && p.s_off == m.s_off + m.run && p.d_off == m.d_off + m.run) {
+                        m.run += p.run;
+                        m.s_stride = m.d_stride = m.run;
+                        continue;
+                    }
+                    if (same && m.rows > 1 && p.rows > 1 && m.run == p.run && m.s_stride == p.s_stride &&
+                        m.d_stride == p.d_stride && p.s_off == m.s_off + m.rows * m.s_stride &&
+                        p.d_off == m.d_off + m.rows * m.d_stride) {
+                        m.rows += p.rows;
+                        continue;
+                    }
+                }
+                merged.push_back(p);
+            }
+            for (const Piece& p : merged)
+                expand(p.slot, p.s_tp, p.s_pp, p.s_ep, tp, pp, d_ep, p.s_off, p.s_stride, p.d_off, p.d_stride, p.rows, p.run);
+            zero_padding(col, d_ep);
+        }
+    }
     return LIVER_OK;
 }
 

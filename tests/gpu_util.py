@@ -4,9 +4,9 @@ import torch
 
 import paper_2605_22014_amd as lv
 
-NP = {0: np.uint16, 1: np.uint32, 2: np.uint32, 3: np.uint32}
-TT = {0: torch.int16, 1: torch.int32, 2: torch.int32, 3: torch.int32}
-SENT = {0: -23131, 1: -1515870811, 2: -1515870811, 3: -1515870811}     # 0xA5 bytes
+NP = {k: (np.uint16 if k % 4 == 0 else np.uint32) for k in range(8)}          # kinds 4..7: expert buffers
+TT = {k: (torch.int16 if k % 4 == 0 else torch.int32) for k in range(8)}
+SENT = {k: (-23131 if k % 4 == 0 else -1515870811) for k in range(8)}          # 0xA5 bytes
 
 
 def to_dev(world):
@@ -21,10 +21,12 @@ def to_host(bufs):
 def alloc_dst(plan, only_used=False):
     out = {}
     for r in range(plan.dst.n_ranks):
-        for k in range(4):
+        for k in range(8):
             if only_used and not lv.liver_plan_buffer_used(plan, 1, r, k):
                 continue
-            n = lv.liver_plan_buffer_bytes(plan, 1, r, k) // (2 if k == 0 else 4)
+            n = lv.liver_plan_buffer_bytes(plan, 1, r, k) // (2 if k % 4 == 0 else 4)
+            if n == 0:                           # expert kinds of a dense model
+                continue
             out[(r, k)] = torch.full((n,), SENT[k], dtype=TT[k], device="cuda")
     return out
 
@@ -60,4 +62,4 @@ def check_against(got_dev, want, plan, what=""):
                 raise AssertionError(f"{what} rank {r} kind {k}: {bad.size} mismatches, first {bad[:4]}: "
                                      f"{g[bad[:4]]} vs {w[bad[:4]]}")
         else:
-            assert (g == (SENT[k] & (0xFFFF if k == 0 else 0xFFFFFFFF))).all(), (what, "unplanned buffer written", r, k)
+            assert (g == (SENT[k] & (0xFFFF if k % 4 == 0 else 0xFFFFFFFF))).all(), (what, "unplanned buffer written", r, k)

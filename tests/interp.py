@@ -9,18 +9,18 @@ import numpy as np
 import oracle
 import paper_2605_22014_amd as lv
 
-DT = {0: np.uint16, 1: np.uint32, 2: np.uint32, 3: np.uint32}
+DT = {k: (np.uint16 if k % 4 == 0 else np.uint32) for k in range(8)}     # kinds 4..7: expert buffers
 
 
 def lv_objects(cfg_or_spec, src, dst, **dst_kw):
     """oracle ModelSpec/Layouts -> binding ModelSpec/Layouts (same fields)."""
     s = cfg_or_spec
     spec = lv.ModelSpec(s.n_layers, s.hidden, s.n_q_heads, s.n_kv_heads, s.ffn, s.vocab, s.max_pos, s.glu,
-                        s.norm_bias, s.linear_bias, s.tied_embed)
+                        s.norm_bias, s.linear_bias, s.tied_embed, s.n_experts)
     a = lv.Layout(src.tp, src.pp, src.dp, src.pad_multiple, vpp=src.vpp, vocab_multiple=src.vocab_multiple, pp_first=src.pp_first,
-                  pp_last=src.pp_last, bucket_elems=src.bucket_elems)
+                  pp_last=src.pp_last, bucket_elems=src.bucket_elems, ep=src.ep)
     b = lv.Layout(dst.tp, dst.pp, dst.dp, dst.pad_multiple, vpp=dst.vpp, vocab_multiple=dst.vocab_multiple, pp_first=dst.pp_first,
-                  pp_last=dst.pp_last, bucket_elems=dst.bucket_elems, **dst_kw)
+                  pp_last=dst.pp_last, bucket_elems=dst.bucket_elems, ep=dst.ep, **dst_kw)
     return spec, a, b
 
 
@@ -42,9 +42,11 @@ def alloc_dst(plan, fill=0xA5):
     n = lv.liver_plan_info(plan).n_dst_ranks
     bufs, counts = {}, {}
     for r in range(n):
-        for k in range(4):
+        for k in range(8):
             nbytes = lv.liver_plan_buffer_bytes(plan, 1, r, k)
-            bufs[(r, k)] = np.full(nbytes // np.dtype(DT[k]).itemsize, fill * 0x01010101 & (0xFFFF if k == 0 else 0xFFFFFFFF), DT[k])
+            if nbytes == 0:                      # expert kinds of a dense model
+                continue
+            bufs[(r, k)] = np.full(nbytes // np.dtype(DT[k]).itemsize, fill * 0x01010101 & (0xFFFF if k % 4 == 0 else 0xFFFFFFFF), DT[k])
             counts[(r, k)] = np.zeros(bufs[(r, k)].size, np.uint8)
     return bufs, counts
 
@@ -61,7 +63,7 @@ def execute(d, src_bufs, dst_bufs, counts, staging=None):
         src = staging.view(DT[d.src_kind]) if d.src_rank < 0 else src_bufs[(d.src_rank, d.src_kind)]
         val = _rows(src, d.src_off, d.src_stride, d.rows, d.run)
         if d.op == lv.OP_CAST_BF16:
-            assert d.src_kind == oracle.MASTER and d.dst_kind == oracle.PARAM
+            assert d.src_kind % 4 == oracle.MASTER and d.dst_kind == d.src_kind - 1
             out[...] = oracle.rne_bf16(val)
         else:
             assert d.op == lv.OP_COPY and (d.dst_rank < 0 or DT[d.src_kind] == DT[d.dst_kind])
@@ -109,7 +111,7 @@ def run_staged(plan, src_bufs, order=None):
 
 def used_dst(plan):
     n = lv.liver_plan_info(plan).n_dst_ranks
-    return {(r, k) for r in range(n) for k in range(4) if lv.liver_plan_buffer_used(plan, 1, r, k)}
+    return {(r, k) for r in range(n) for k in range(8) if lv.liver_plan_buffer_used(plan, 1, r, k)}
 
 
 def emulate_direct(plan, src_bufs):

@@ -35,14 +35,37 @@ def layer_param_sizes(spec, TP, l):
     out.append((p + "ln2.w", H))
     if spec.norm_bias:
         out.append((p + "ln2.b", H))
+    if spec.n_experts:                      # mixture of experts: the dense buffer holds only the router
+        out.append((p + "router.w", spec.n_experts * H))
+    else:
+        out += ffn_param_sizes(spec, TP, p)
+    return out
+
+
+def ffn_param_sizes(spec, TP, p):
+    """fc1 (+bias), fc2 (+bias) of the FFN whose physical names start with p."""
+    H, hd, Q, KV, F, V = dims(spec)
     n_fc1 = 2 * F if spec.glu else F
-    out.append((p + "fc1.w", n_fc1 * H // TP))
+    out = [(p + "fc1.w", n_fc1 * H // TP)]
     if spec.linear_bias:
         out.append((p + "fc1.b", n_fc1 // TP))
     out.append((p + "fc2.w", H * F // TP))
     if spec.linear_bias:
         out.append((p + "down.b", H))
     return out
+
+
+def group_size(lay, ep=None):
+    """Ranks sharing one flat buffer: all DP ranks for the dense buffers, DP/EP for the expert buffers."""
+    return lay.dp if ep is None else lay.dp // lay.ep
+
+
+def stage_layer_list(spec, lay, pp):
+    PP, vpp, first, last = lay.pp, lay.vpp, lay.pp_first, lay.pp_last
+    if first or last:
+        return list(range(*uneven_stage_range(spec.n_layers, PP, pp, first, last)))
+    c = spec.n_layers // (PP * vpp)          # layers per model chunk; stage pp holds chunks pp, pp+PP, ...
+    return [l for v in range(vpp) for l in range((v * PP + pp) * c, (v * PP + pp) * c + c)]
 
 
 def vocab_rows(spec, TP, vm=0):
@@ -61,25 +84,24 @@ def uneven_stage_range(L, PP, pp, first, last):
     return lo, lo + count(pp)
 
 
-def stage_param_sizes(spec, lay, pp):
+def stage_param_sizes(spec, lay, pp, ep=None):
     """[(physical name, element count)] of stage pp on one TP rank, in flat-buffer order.
-    `lay` is any object with tp, pp, dp, pad_multiple, vpp, vocab_multiple, pp_first, pp_last, bucket_elems."""
+    `lay` is any object with tp, pp, dp, pad_multiple, vpp, vocab_multiple, pp_first, pp_last, bucket_elems, ep.
+    ep = None: the dense buffer.  ep = e: the expert buffer of expert-parallel index e (experts
+    e*E/EP .. (e+1)*E/EP - 1 of every layer of the stage, layer by layer)."""
     H, hd, Q, KV, F, V = dims(spec)
     TP, PP, vpp, vm, first, last = lay.tp, lay.pp, lay.vpp, lay.vocab_multiple, lay.pp_first, lay.pp_last
+    if ep is not None:
+        per = spec.n_experts // lay.ep
+        return [x for l in stage_layer_list(spec, lay, pp) for e in range(ep * per, ep * per + per)
+                for x in ffn_param_sizes(spec, TP, f"L{l}.x{e}.")]
     out = []
     if pp == 0:
         out.append(("embed.word", vocab_rows(spec, TP, vm) * H))
         if spec.max_pos:
             out.append(("embed.pos", spec.max_pos * H))
-    if first or last:
-        for l in range(*uneven_stage_range(spec.n_layers, PP, pp, first, last)):
-            out += layer_param_sizes(spec, TP, l)
-        vpp = 0
-    c = spec.n_layers // (PP * max(vpp, 1))  # layers per model chunk; stage pp holds chunks pp, pp+PP, ...
-    for v in range(vpp):
-        lo = (v * PP + pp) * c
-        for l in range(lo, lo + c):
-            out += layer_param_sizes(spec, TP, l)
+    for l in stage_layer_list(spec, lay, pp):
+        out += layer_param_sizes(spec, TP, l)
     if pp == PP - 1:
         out.append(("final_norm.w", H))
         if spec.norm_bias:
@@ -91,12 +113,12 @@ def stage_param_sizes(spec, lay, pp):
     return out
 
 
-def bucket_table(spec, lay, pp):
+def bucket_table(spec, lay, pp, ep=None):
     """[(start, used, padded)] of the buckets of stage pp's flat buffer.  Parameters are appended in order; a
     bucket closes after the parameter that brings it to >= bucket_elems elements (bucket_elems 0: one bucket);
     every bucket is zero-padded to a multiple of DP*pad_multiple elements."""
-    sizes = stage_param_sizes(spec, lay, pp)
-    q = lay.dp * lay.pad_multiple
+    sizes = stage_param_sizes(spec, lay, pp, ep)
+    q = group_size(lay, ep) * lay.pad_multiple
     out, start, used = [], 0, 0
     for i, (_, n) in enumerate(sizes):
         used += n
@@ -107,28 +129,29 @@ def bucket_table(spec, lay, pp):
     return out
 
 
-def n_local(spec, lay, pp):
+def n_local(spec, lay, pp, ep=None):
     """End of the last parameter in the flat buffer (interior bucket padding included)."""
-    start, used, _ = bucket_table(spec, lay, pp)[-1]
+    start, used, _ = bucket_table(spec, lay, pp, ep)[-1]
     return start + used
 
 
-def n_pad(spec, lay, pp):
-    start, _, padded = bucket_table(spec, lay, pp)[-1]
+def n_pad(spec, lay, pp, ep=None):
+    start, _, padded = bucket_table(spec, lay, pp, ep)[-1]
     return start + padded
 
 
-def shard_location(spec, lay, pp):
+def shard_location(spec, lay, pp, ep=None):
     """(dp_of, local_of): for every flat position 0..N_pad-1 of the fp32 buffers, the DP rank that holds it and
-    its offset in that rank's buffer.  Each bucket is cut into DP equal slices; a rank's buffer is the
-    concatenation of its slice of every bucket."""
-    npad = n_pad(spec, lay, pp)
+    its offset in that rank's buffer.  Each bucket is cut into equal slices, one per rank sharing the buffer
+    (all DP ranks; for an expert buffer the DP ranks ep, ep+EP, ...); a rank's buffer is the concatenation of
+    its slice of every bucket."""
+    npad = n_pad(spec, lay, pp, ep)
     dp_of, local_of = np.zeros(npad, np.int64), np.zeros(npad, np.int64)
-    prefix = 0
-    for start, _, padded in bucket_table(spec, lay, pp):
-        Sb = padded // lay.dp
+    prefix, g = 0, group_size(lay, ep)
+    for start, _, padded in bucket_table(spec, lay, pp, ep):
+        Sb = padded // g
         k = np.arange(padded, dtype=np.int64)
-        dp_of[start:start + padded] = k // Sb
+        dp_of[start:start + padded] = k // Sb if ep is None else ep + lay.ep * (k // Sb)
         local_of[start:start + padded] = prefix + k % Sb
         prefix += Sb
     return dp_of, local_of
@@ -142,11 +165,13 @@ def owner(spec, lay, tp, phys, k):
     k = np.asarray(k, np.int64)
     base = phys.split("(")[0]
     pre = base[:base.index(".") + 1] if base.startswith("L") else ""
+    if base[len(pre):].startswith("x"):                          # expert FFN: "L3.x5.fc1.w"
+        pre = base[:base.index(".", len(pre)) + 1]
     leaf = base[len(pre):]
     names = np.empty(k.shape, dtype=object)
 
     if leaf in ("ln1.w", "ln1.b", "ln2.w", "ln2.b", "o.b", "down.b", "final_norm.w",
-                "final_norm.b", "embed.pos"):                    # replicated
+                "final_norm.b", "embed.pos", "router.w"):        # replicated
         names[:] = base
         return names, k
     if leaf in ("embed.word", "lm_head.w"):                      # column-parallel [V, H], maybe padded
@@ -203,7 +228,7 @@ def owner(spec, lay, tp, phys, k):
     raise KeyError(phys)
 
 
-def column_ownership(spec, lay, tp, pp):
+def column_ownership(spec, lay, tp, pp, ep=None):
     """For flat positions 0..N_pad-1 of rank column (tp, pp): (names, idx, canonical).
 
     names[k] is None where the position holds padding (bucket padding, tail padding, vocabulary padding rows).
@@ -211,18 +236,20 @@ def column_ownership(spec, lay, tp, pp):
     parameters on tp > 0, replicated k / v heads on all but the first rank of their group, and the
     tied-embedding copy."""
     TP = lay.tp
-    npad = n_pad(spec, lay, pp)
+    npad = n_pad(spec, lay, pp, ep)
     names = np.full(npad, None, dtype=object)
     idx = np.zeros(npad, np.int64)
     canon = np.zeros(npad, bool)
-    sizes = stage_param_sizes(spec, lay, pp)
-    q = lay.dp * lay.pad_multiple
+    sizes = stage_param_sizes(spec, lay, pp, ep)
+    q = group_size(lay, ep) * lay.pad_multiple
     pos, used = 0, 0
     for phys, n in sizes:
         nm, ix = owner(spec, lay, tp, phys, np.arange(n, dtype=np.int64))
         leaf = phys.split(".", 1)[1] if phys.startswith("L") else phys
+        if leaf.startswith("x"):
+            leaf = leaf.split(".", 1)[1]
         replicated = leaf in ("ln1.w", "ln1.b", "ln2.w", "ln2.b", "o.b", "down.b", "final_norm.w",
-                              "final_norm.b", "embed.pos")
+                              "final_norm.b", "embed.pos", "router.w")
         ok = np.full(n, not (replicated and tp > 0) and "(tied copy)" not in phys)
         if leaf in ("qkv.w", "qkv.b") and spec.n_kv_heads % TP and tp % (TP // spec.n_kv_heads):
             ok &= np.char.endswith(nm.astype(str), ("q." + leaf[-1]))      # replicated k / v: read from part 0 only

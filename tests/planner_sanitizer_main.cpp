@@ -60,5 +60,10 @@ int main() {
     c.pp_first = 1, c.pp_last = 3;
     b.flags = 0;  // as a source layout
     bad += plan_one("odd: uneven stages", odd, b, c, 512);
+    liver_model_spec_t moe{4, 32, 4, 2, 24, 40, 0, LIVER_GLU | LIVER_LINEAR_BIAS, 8};   // 8 experts per layer
+    liver_layout_t ma = lay(2, 2, 4, 4), mb = lay(1, 1, 6, 8);
+    ma.ep = 4, ma.bucket_elems = 900;
+    mb.ep = 2, mb.flags = LIVER_DERIVE_BF16, mb.only_dp = 3;
+    bad += plan_one("moe: ep 4 -> ep 2, buckets, one target rank, derive", moe, ma, mb, 1024);
     return bad ? 1 : 0;
 }

@@ -10,7 +10,7 @@ import pytest
 import liver_synth as synth
 import oracle
 import ownership as own
-from util import cfg_objects, make_world, assert_same, corrupt_replicas
+from util import cfg_objects, make_world, assert_same, corrupt_replicas, buffers_of
 
 SPECS = {
     "tiny_gpt": oracle.ModelSpec(**synth.CONFIGS["tiny_gpt"]["spec"]),
@@ -24,6 +24,8 @@ SPECS = {
     "odd_vocab_tied": oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=4, n_kv_heads=4, ffn=32, vocab=50,
                                        max_pos=8, tied_embed=True),
     "odd_vocab_head": oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=4, n_kv_heads=4, ffn=32, vocab=37, glu=True),
+    "moe": oracle.ModelSpec(n_layers=2, hidden=32, n_q_heads=4, n_kv_heads=2, ffn=24, vocab=32, glu=True,
+                            linear_bias=True, n_experts=4),
     "mqa_tied": oracle.ModelSpec(n_layers=4, hidden=32, n_q_heads=4, n_kv_heads=1, ffn=64, vocab=32,
                                  tied_embed=True),
 }
@@ -32,7 +34,8 @@ LAYOUTS = [(1, 1, 1, 128), (2, 1, 2, 128), (1, 2, 2, 128), (2, 2, 3, 4), (4, 2, 
            (8, 1, 2, 4),                                            # TP 8 > n_kv: replicated kv heads
            (2, 2, 2, 4, 1, 8), (4, 1, 1, 1, 1, 4), (1, 1, 2, 1, 1, 16), (4, 2, 3, 128, 1, 32),   # 6th: vocab_multiple
            (1, 2, 2, 4, 1, 0, 1, 0), (2, 2, 1, 1, 1, 0, 3, 1), (1, 3, 1, 1, 1, 0, 1, 1),         # 7th, 8th: pp_first, pp_last
-           (2, 1, 3, 4, 1, 0, 0, 0, 3000), (1, 2, 2, 128, 1, 0, 0, 0, 1), (2, 2, 2, 1, 2, 8, 0, 0, 5000)]   # 9th: bucket_elems
+           (2, 1, 3, 4, 1, 0, 0, 0, 3000), (1, 2, 2, 128, 1, 0, 0, 0, 1), (2, 2, 2, 1, 2, 8, 0, 0, 5000),   # 9th: bucket_elems
+           (2, 1, 4, 4, 1, 0, 0, 0, 0, 2), (1, 2, 4, 1, 1, 0, 0, 0, 900, 4), (2, 2, 2, 8, 1, 0, 0, 0, 0, 1)]  # 10th: ep
 
 
 def _cases():
@@ -43,7 +46,7 @@ def _cases():
                 oracle.check_supported(spec, lay)
             except ValueError:
                 continue
-            yield pytest.param(spec, lay, id=f"{sname}-tp{tp}pp{pp}dp{dp}pm{pm}v{lay.vpp}vm{lay.vocab_multiple}f{lay.pp_first}l{lay.pp_last}b{lay.bucket_elems}")
+            yield pytest.param(spec, lay, id=f"{sname}-tp{tp}pp{pp}dp{dp}pm{pm}v{lay.vpp}vm{lay.vocab_multiple}f{lay.pp_first}l{lay.pp_last}b{lay.bucket_elems}e{lay.ep}")
 
 
 def _tensor_ordinal_state(spec):
@@ -62,24 +65,30 @@ def test_split_matches_ownership(spec, lay):
     w_idx = make_world(spec, lay, synth.index_encoded_state(shapes, half=0), poison=False)
     w_hi = make_world(spec, lay, synth.index_encoded_state(shapes, half=1), poison=False)
     w_ord = make_world(spec, lay, _tensor_ordinal_state(spec), poison=False)
-    for pp in range(lay.pp):
-        npad = own.n_pad(spec, lay, pp)
-        dp_of, local_of = own.shard_location(spec, lay, pp)
+    for base, ep in buffers_of(spec, lay):                                # dense buffers, then one expert buffer per ep
+      for pp in range(lay.pp):
+        npad = own.n_pad(spec, lay, pp, ep)
+        dp_of, local_of = own.shard_location(spec, lay, pp, ep)
+        group = list(range(lay.dp)) if ep is None else list(range(ep, lay.dp, lay.ep))
         for tp in range(lay.tp):
-            names, idx, _ = own.column_ownership(spec, lay, tp, pp)       # padding: name None, index 0
+            names, idx, _ = own.column_ownership(spec, lay, tp, pp, ep)   # padding: name None, index 0
             exp_idx = idx
             exp_ord = np.array([ordinal.get(n, 0) for n in names], np.int64)
             for dp in range(lay.dp):
                 r = lay.rank(tp, pp, dp)
-                assert np.array_equal(w_idx[(r, oracle.PARAM)], (exp_idx & 0xFFFF).astype(np.uint16))
-                assert np.array_equal(w_hi[(r, oracle.PARAM)], ((exp_idx >> 16) & 0xFFFF).astype(np.uint16))
-                assert np.array_equal(w_ord[(r, oracle.PARAM)], exp_ord.astype(np.uint16))
+                if dp not in group:                                       # ranks of another expert-parallel index
+                    continue
+                assert np.array_equal(w_idx[(r, base)], (exp_idx & 0xFFFF).astype(np.uint16))
+                assert np.array_equal(w_hi[(r, base)], ((exp_idx >> 16) & 0xFFFF).astype(np.uint16))
+                assert np.array_equal(w_ord[(r, base)], exp_ord.astype(np.uint16))
                 mine = np.flatnonzero(dp_of == dp)
-                assert np.array_equal(local_of[mine], np.arange(npad // lay.dp))      # a rank's buffer is dense
-                for k in (oracle.MASTER, oracle.ADAM_M, oracle.ADAM_V):
-                    assert w_idx[(r, k)].shape == (npad // lay.dp,)
+                assert np.array_equal(local_of[mine], np.arange(npad // len(group)))      # a rank's buffer is dense
+                for k in (base + 1, base + 2, base + 3):
+                    assert w_idx[(r, k)].shape == (npad // len(group),)
                     assert np.array_equal(w_idx[(r, k)], exp_idx[mine].astype(np.uint32))
                     assert np.array_equal(w_ord[(r, k)], exp_ord[mine].astype(np.uint32))
+    n_bufs = lay.n_ranks * (8 if spec.n_experts else 4)
+    assert len(w_idx) == n_bufs                                            # every rank holds every kind exactly once
 
 
 @pytest.mark.parametrize("spec,lay", list(_cases()))
@@ -89,11 +98,13 @@ def test_gather_inverts_split(spec, lay):
     shapes = oracle.logical_tensors(spec)
     state = synth.logical_state(shapes, synth.SEED_BASE, "uniform")
     world = make_world(spec, lay, state, poison=True)
-    for k in oracle.KINDS:
+    seen = []
+    for k in oracle.kinds_of(spec):
         back = oracle.gather_logical(spec, lay, k, oracle.dict_reader(world))
-        assert list(back) == list(shapes)
-        for n in shapes:
-            assert np.array_equal(back[n], state[k][n]), (k, n)
+        seen += list(back) if k % 4 == 0 else []
+        for n in back:
+            assert np.array_equal(back[n], state[k % 4][n]), (k, n)
+    assert sorted(seen) == sorted(shapes)                  # dense and expert kinds together cover every tensor
 
 
 def test_gather_reads_lowest_replica():
@@ -118,8 +129,8 @@ def test_gather_detects_broken_tiling(monkeypatch):
     world = make_world(spec, lay, synth.logical_state(oracle.logical_tensors(spec), 3, "uniform"))
     real = oracle.reshard_oracle.stage_view
 
-    def broken(spec_, lay_, tp, pp):
-        sv = real(spec_, lay_, tp, pp)
+    def broken(spec_, lay_, tp, pp, ep=None):
+        sv = real(spec_, lay_, tp, pp, ep)
         sv.params[0].canonical = False          # nobody provides embed.word any more
         return sv
     monkeypatch.setattr(oracle.reshard_oracle, "stage_view", broken)
@@ -195,3 +206,28 @@ def test_bucket_boundaries_closed_form():
     # DP rank 1 of 3 holds the middle third of every bucket, concatenated
     assert oracle.dp_pieces(sv3, lay3, 0, 864)[1::3] == [(1, 0, 120, 120), (1, 120, 472, 112), (1, 232, 752, 56)]
     assert own.bucket_table(spec, lay3, 0) == [(0, 360, 360), (360, 328, 336), (696, 168, 168)]
+
+
+def test_expert_buffers_closed_form():
+    """MoE: 4 experts, EP 2 inside DP 4: DP ranks 0, 2 hold experts 0-1 and ranks 1, 3 hold experts 2-3; the
+    expert buffer of a rank lists, layer by layer, its experts' fc1 / fc2 (TP-split like a dense FFN) and is
+    optimizer-sharded over the two ranks that hold the same experts; the dense buffer keeps only the router."""
+    spec = SPECS["moe"]
+    lay = oracle.Layout(2, 1, 4, 4, ep=2)
+    H, F = 32, 24
+    per_expert = 2 * F * H // 2 + 2 * F // 2 + H * F // 2 + H           # fc1.w, fc1.b, fc2.w, down.b on one of 2 TP ranks
+    for ep in (0, 1):
+        sv = oracle.stage_view(spec, lay, 1, 0, ep)
+        assert sv.dp_ranks == [ep, ep + 2] and sv.n_local == 2 * 2 * per_expert            # 2 layers x 2 local experts
+        assert [p.name for p in sv.params[:4]] == [f"L0.x{2 * ep}.fc1.w", f"L0.x{2 * ep}.fc1.b", f"L0.x{2 * ep}.fc2.w",
+                                                   f"L0.x{2 * ep}.down.b"]
+        assert sv.n_pad % (2 * 4) == 0 and sv.S == sv.n_pad // 2
+    dense = oracle.stage_view(spec, lay, 0, 0)
+    assert dense.dp_ranks == [0, 1, 2, 3] and not any(".x" in p.name for p in dense.params)
+    assert [p.name for p in dense.params if "router" in p.name] == ["L0.router.w", "L1.router.w"]
+    assert oracle.buffer_elems(spec, lay, 0, 0, oracle.EXPERT_MASTER, dp=3) == oracle.stage_view(spec, lay, 0, 0, 1).S
+    for bad in (oracle.Layout(1, 1, 4, 4, ep=3), oracle.Layout(1, 1, 2, 4, ep=4)):
+        with pytest.raises(ValueError):
+            oracle.stage_view(spec, bad, 0, 0)
+    with pytest.raises(ValueError):
+        oracle.stage_view(SPECS["mqa_tied"], oracle.Layout(1, 1, 2, 4, ep=2), 0, 0)         # ep without experts

@@ -24,6 +24,9 @@ VOC = oracle.ModelSpec(n_layers=2, hidden=16, n_q_heads=4, n_kv_heads=4, ffn=16,
                        tied_embed=True)          # 50 rows never divide evenly: padded per world
 VOCH = oracle.ModelSpec(n_layers=2, hidden=16, n_q_heads=4, n_kv_heads=2, ffn=16, vocab=37, glu=True)
 
+MOE = oracle.ModelSpec(n_layers=2, hidden=16, n_q_heads=4, n_kv_heads=2, ffn=12, vocab=16, glu=True,
+                       linear_bias=True, n_experts=4)        # router in the dense buffers, experts in kinds 4..7
+
 BRUTE = [
     (ODD, (2, 1, 2, 4), (1, 2, 3, 1)),
     (ODD, (1, 2, 3, 1), (2, 2, 1, 4)),
@@ -48,6 +51,9 @@ BRUTE = [
     (ODD, (1, 2, 3, 1), (2, 2, 2, 4, 1, 0, 0, 0, 500)),                       # one bucket -> bucketed, padding inside
     (ODD6, (3, 2, 3, 4, 1, 0, 0, 0, 900), (2, 3, 2, 8, 1, 0, 0, 0, 400)),     # buckets on both sides, different cuts
     (VOC, (2, 1, 2, 4, 1, 8, 0, 0, 300), (1, 2, 3, 4, 1, 4, 0, 0, 1)),        # with vocabulary padding; one bucket per parameter
+    (MOE, (2, 1, 4, 4, 1, 0, 0, 0, 0, 2), (1, 2, 2, 1, 1, 0, 0, 0, 0, 1)),    # EP 2 -> EP 1 (10th = ep): experts gathered
+    (MOE, (1, 1, 2, 1, 1, 0, 0, 0, 0, 1), (2, 2, 4, 4, 1, 0, 0, 0, 0, 4)),    # EP 1 -> EP 4: one expert per DP rank
+    (MOE, (2, 2, 4, 1, 1, 0, 0, 0, 500, 4), (2, 1, 6, 4, 1, 0, 0, 0, 300, 2)),  # EP 4 -> EP 2 with buckets, DP 4 -> 6 (replicas corrupted)
 ]
 
 
@@ -60,6 +66,7 @@ def test_brute_force_tiny(case, derive):
     if case % 2:
         corrupt_replicas(spec, src, world)      # the copies that must not be read differ
     got = oracle.reshard_state(spec, src, dst, world, derive_bf16=derive)
+    assert len(got) == dst.n_ranks * len(oracle.kinds_of(spec))
     want = brute_reshard(spec, src, dst, world, derive=derive)
     assert_same(got, want, f"case {case}")
 

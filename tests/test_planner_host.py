@@ -36,9 +36,9 @@ def _check(spec, src, dst, world, chunk_bytes, derive=False, **dst_kw):
         for pp in range(lay.pp):
             for tp in range(lay.tp):
                 for dp in range(lay.dp):
-                    for k in oracle.KINDS:
+                    for k in oracle.kinds_of(spec):
                         n = lv.liver_plan_buffer_bytes(plan, side, lay.rank(tp, pp, dp), k)
-                        assert n == oracle.buffer_elems(spec, lay, tp, pp, k) * np.dtype(DT[k]).itemsize
+                        assert n == oracle.buffer_elems(spec, lay, tp, pp, k, dp) * np.dtype(DT[k]).itemsize
     used = used_dst(plan)
     results = [run_direct(plan, world), run_staged(plan, world),
                run_staged(plan, world, order=list(range(info.n_chunks))[::-1]),
@@ -51,7 +51,7 @@ def _check(spec, src, dst, world, chunk_bytes, derive=False, **dst_kw):
             elif counts is not None:
                 assert not counts[key].any(), ("unplanned buffer written", key)
             else:
-                assert (got[key] == (0xA5A5 if key[1] == 0 else 0xA5A5A5A5)).all(), ("unplanned buffer written", key)
+                assert (got[key] == (0xA5A5 if key[1] % 4 == 0 else 0xA5A5A5A5)).all(), ("unplanned buffer written", key)
     assert info.n_chunks == -(-info.stream_bytes // chunk_bytes)
     return plan, info, used
 
@@ -65,7 +65,7 @@ def test_tiny_odd_models(case, derive):
     if case % 2:
         corrupt_replicas(spec, src, world)
     _, info, used = _check(spec, src, dst, world, 256 * (1 + case), derive)
-    assert len(used) == dst.n_ranks * 4
+    assert len(used) == dst.n_ranks * len(oracle.kinds_of(spec))
 
 
 @pytest.mark.parametrize("chunk_bytes", [4096, 1 << 20, 1 << 30])
@@ -335,3 +335,20 @@ def test_source_side_restriction_partitions_the_work():
             execute(d, None, out, counts, staging)
     for key in out:
         assert np.array_equal(out[key], want[key]) and (counts[key] == 1).all(), key
+
+
+@pytest.mark.parametrize("kw", [dict(only_dp=3), dict(only_tp=1, only_dp=0), dict(kinds=(1, 2)), dict(only_pp=1, kinds=(0,))])
+@pytest.mark.parametrize("derive", [False, True])
+def test_filtered_plans_mixture_of_experts(kw, derive):
+    """Restricted plans of an MoE model: only_dp = 3 with EP 2 plans the expert buffers of index 1 only."""
+    from test_oracle_reshard import MOE
+    src, dst = oracle.Layout(2, 1, 2, 4, ep=2), oracle.Layout(2, 2, 4, 1, ep=2, bucket_elems=400)
+    world = make_world(MOE, src, tiny_state(MOE, seed=5))
+    _, info, used = _check(MOE, src, dst, world, 512, derive, **kw)
+    exp = set()
+    for pp in range(dst.pp):
+        for tp in range(dst.tp):
+            for dp in range(dst.dp):
+                if kw.get("only_tp", tp) == tp and kw.get("only_pp", pp) == pp and kw.get("only_dp", dp) == dp:
+                    exp |= {(dst.rank(tp, pp, dp), k + 4 * f) for k in kw.get("kinds", (0, 1, 2, 3)) for f in (0, 1)}
+    assert used == exp

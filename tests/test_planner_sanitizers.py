@@ -21,4 +21,4 @@ def test_planner_under_asan_ubsan(tmp_path):
     env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1", LD_PRELOAD="")
     run = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
     assert run.returncode == 0, (run.stdout[-2000:], run.stderr[-3000:])
-    assert run.stdout.count(": ok,") == 5, run.stdout
+    assert run.stdout.count(": ok,") == 6, run.stdout
