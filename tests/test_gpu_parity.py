@@ -277,3 +277,18 @@ def test_source_side_restriction():
         lv.liver_unpack(plans[0], c, staging, out)
     torch.cuda.synchronize()
     check_against(out, want, full, "staged, packed by source-restricted plans")
+
+
+def test_mixture_of_experts_medium():
+    """An MoE shape with aligned sizes (vector paths): 8 experts, EP 4 -> 2, TP 2 -> 1, DP 4 -> 4, buckets."""
+    print("moe medium", flush=True)
+    spec = oracle.ModelSpec(n_layers=4, hidden=512, n_q_heads=8, n_kv_heads=4, ffn=1024, vocab=4096, glu=True, n_experts=8)
+    src = oracle.Layout(2, 2, 4, 128, ep=4, bucket_elems=3_000_000)
+    dst = oracle.Layout(1, 1, 4, 128, ep=2, bucket_elems=5_000_000)
+    world = make_world(spec, src, synth.logical_state(oracle.logical_tensors(spec), 21, "normal"))
+    for derive in (False, True):
+        want = oracle.reshard_state(spec, src, dst, world, derive_bf16=derive)
+        plan = _plan(spec, src, dst, 8 << 20, derive)
+        dev = to_dev(world)
+        check_against(run_direct(plan, dev), want, plan, f"moe direct derive={derive}")
+        check_against(run_staged(plan, dev), want, plan, f"moe staged derive={derive}")
