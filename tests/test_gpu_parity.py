@@ -292,3 +292,21 @@ def test_mixture_of_experts_medium():
         dev = to_dev(world)
         check_against(run_direct(plan, dev), want, plan, f"moe direct derive={derive}")
         check_against(run_staged(plan, dev), want, plan, f"moe staged derive={derive}")
+
+
+def test_concurrent_streams_share_a_plan(gpt2):
+    """The data calls are re-entrant: the same plan runs on two streams at once into two different target sets
+    (buffer pointers travel in the kernel arguments, nothing in the plan is written)."""
+    cfg, spec, src, dst, world, want, dev = gpt2
+    print("two streams, one plan", flush=True)
+    plan = _plan(spec, src, dst, cfg["chunk_bytes"])
+    out_a, out_b = alloc_dst(plan), alloc_dst(plan)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        lv.liver_reshard(plan, dev, out_a, sa)
+        lv.liver_reshard(plan, dev, out_b, sb)
+    sa.synchronize()
+    sb.synchronize()
+    check_against(out_a, want, plan, "stream a")
+    check_against(out_b, want, plan, "stream b")
