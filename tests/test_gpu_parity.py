@@ -310,3 +310,19 @@ def test_concurrent_streams_share_a_plan(gpt2):
     sb.synchronize()
     check_against(out_a, want, plan, "stream a")
     check_against(out_b, want, plan, "stream b")
+
+
+def test_extra_fp32_state_rides_a_one_kind_plan():
+    """Any further fp32 state that is sliced over DP like the Adam moments (reduce-scattered gradient shards,
+    Section 4.1's optional accumulators) is resharded by a plan restricted to ONE fp32 kind whose table
+    slots point at that state; only those slots need to be filled."""
+    print("extra fp32 state through kind_mask", flush=True)
+    spec = oracle.ModelSpec(n_layers=4, hidden=64, n_q_heads=8, n_kv_heads=4, ffn=96, vocab=128, glu=True)
+    src, dst = oracle.Layout(4, 2, 4, 128), oracle.Layout(2, 4, 6, 128)
+    grads = make_world(spec, src, synth.logical_state(oracle.logical_tensors(spec), 77, "normal"), kinds=(synth.ADAM_M,))
+    assert {k for _, k in grads} == {synth.ADAM_M}
+    want = oracle.reshard_state(spec, src, dst, grads, kinds=(synth.ADAM_M,))
+    plan = _plan(spec, src, dst, 4096, kinds=(synth.ADAM_M,))
+    dev = to_dev(grads)
+    check_against(run_direct(plan, dev, only_used=True), want, plan, "direct")
+    check_against(run_staged(plan, dev, only_used=True), want, plan, "staged")
