@@ -71,7 +71,7 @@ def main():
 
     # ---- buffers: every used source and target buffer, allocated ALTERNATELY (source, target, source, ...)
     # and SPREAD over the whole HBM by unused gap allocations between them.  Where the caller's buffers sit in
-    # HBM changes the bandwidth of any copy on this part by ~10 % (measured, DESIGN.md section 7): in the first
+    # HBM changes the bandwidth of any copy on this part by ~10 % (measured): in the first
     # process on a freshly booted box "all sources, then all targets, back to back" runs this reshard at
     # 5.6 TB/s; spread over the HBM it runs at 6.25 TB/s in every process.  The library does not own the
     # buffers, so the benchmark places them well and says so.
