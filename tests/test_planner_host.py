@@ -352,3 +352,35 @@ def test_filtered_plans_mixture_of_experts(kw, derive):
                 if kw.get("only_tp", tp) == tp and kw.get("only_pp", pp) == pp and kw.get("only_dp", dp) == dp:
                     exp |= {(dst.rank(tp, pp, dp), k + 4 * f) for k in kw.get("kinds", (0, 1, 2, 3)) for f in (0, 1)}
     assert used == exp
+
+
+def test_planning_from_many_threads_gives_identical_plans():
+    """The planner keeps no shared mutable state: concurrent liver_plan_create calls (ctypes releases the GIL)
+    return plans with identical descriptors, and error text stays per thread."""
+    import threading
+    cfg, spec, src, dst = cfg_objects("gpt2_small")
+    s, a, b = lv_objects(spec, src, dst)
+
+    def fingerprint(plan):
+        return [(d.op, d.chunk, d.src_rank, d.src_kind, d.src_off, d.src_stride, d.dst_rank, d.dst_kind, d.dst_off, d.dst_stride, d.rows, d.run)
+                for d in (lv.liver_plan_desc(plan, lv.LIST_DIRECT, i) for i in range(0, lv.liver_plan_desc_count(plan, lv.LIST_DIRECT), 7))]
+
+    want = fingerprint(lv.liver_plan_create(s, a, b, cfg["chunk_bytes"]))
+    out, errs = [None] * 8, []
+
+    def work(i):
+        try:
+            if i % 4 == 3:                                   # an error path running next to the good ones
+                with pytest.raises(lv.LiverError):
+                    lv.liver_plan_create(s, a, b, 3)
+                out[i] = want
+            else:
+                out[i] = fingerprint(lv.liver_plan_create(s, a, b, cfg["chunk_bytes"]))
+        except BaseException as e:                           # noqa: BLE001 - reported below
+            errs.append(repr(e))
+
+    ts = [threading.Thread(target=work, args=(i,)) for i in range(8)]
+    [t.start() for t in ts]
+    [t.join() for t in ts]
+    assert not errs, errs
+    assert all(o == want for o in out)
