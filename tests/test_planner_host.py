@@ -196,6 +196,20 @@ def test_big_config_plan_statistics(name):
                 cap = cfg["chunk_bytes"] if rank < 0 else lv.liver_plan_buffer_bytes(plan, side, rank, kind)
                 assert 0 <= off and end <= cap
                 assert (off * eb) % 16 == 0 and (d.run * eb) % 16 == 0 and (d.rows == 1 or (stride * eb) % 16 == 0)
+    # the row runs of the direct list, and of all unpack chunks together, tile every planned target buffer
+    # exactly: sorted by start, each run begins where the previous one ends, from 0 to the buffer's end
+    for which in (lv.LIST_DIRECT, lv.LIST_UNPACK):
+        runs = {}
+        for d in descs(plan, which):
+            starts = d.dst_off + d.dst_stride * np.arange(d.rows, dtype=np.int64)
+            runs.setdefault((d.dst_rank, d.dst_kind), []).append(np.stack([starts, starts + d.run], 1))
+        planned = [(r, k) for r in range(dst.n_ranks) for k in range(4) if lv.liver_plan_buffer_used(plan, 1, r, k)]
+        assert sorted(runs) == planned
+        for (r, k), parts in runs.items():
+            iv = np.concatenate(parts)
+            iv = iv[np.argsort(iv[:, 0], kind="stable")]
+            assert iv[0, 0] == 0 and (iv[1:, 0] == iv[:-1, 1]).all(), (which, r, k)
+            assert iv[-1, 1] * (2 if k == 0 else 4) == lv.liver_plan_buffer_bytes(plan, 1, r, k), (which, r, k)
 
 
 def test_error_codes():
