@@ -398,3 +398,49 @@ def test_planning_from_many_threads_gives_identical_plans():
     [t.join() for t in ts]
     assert not errs, errs
     assert all(o == want for o in out)
+
+
+def _owners_of(spec, lay, rank, kind, offs):
+    """(name, logical index) of elements `offs` of buffer (rank, kind) by the closed-form ownership formulas
+    (unbucketed layouts: a rank's fp32 buffer is slice dp of the column's flat buffer)."""
+    import ownership as own
+    tp, dp, pp = rank % lay.tp, (rank // lay.tp) % lay.dp, rank // (lay.tp * lay.dp)
+    flat = np.asarray(offs, np.int64) + (0 if kind == 0 else dp * (own.n_pad(spec, lay, pp) // lay.dp))
+    sizes = own.stage_param_sizes(spec, lay, pp)
+    starts = np.concatenate([[0], np.cumsum([n for _, n in sizes])])
+    j = np.searchsorted(starts, flat, side="right") - 1
+    names, idx = np.full(flat.shape, None, dtype=object), np.zeros(flat.shape, np.int64)
+    for p in np.unique(j[j < len(sizes)]):
+        m = j == p
+        names[m], idx[m] = own.owner(spec, lay, tp, sizes[p][0], flat[m] - starts[p])
+    return names, idx
+
+
+@pytest.mark.parametrize("name", ["llama7b", "llama13b_dp", "llama70b_rank"])
+def test_full_size_descriptors_agree_with_ownership_formulas(name):
+    """At the real shapes: first, last and 30 random elements of every direct descriptor move between
+    two positions that the ownership formulas give the SAME logical element; zero descriptors hit padding."""
+    cfg, spec, src, dst = cfg_objects(name)
+    only = cfg["only"] or {}
+    s, a, b = lv_objects(spec, src, dst, kinds=cfg["kinds"], **{"only_" + k: v for k, v in only.items()})
+    plan = lv.liver_plan_create(s, a, b, cfg["chunk_bytes"])
+    rng = np.random.default_rng(5)
+    groups = {}
+    for d in descs(plan, lv.LIST_DIRECT):
+        r = np.concatenate([[0, d.rows - 1], rng.integers(d.rows, size=30)]).astype(np.int64)
+        c = np.concatenate([[0, d.run - 1], rng.integers(d.run, size=30)]).astype(np.int64)
+        key = (d.op, d.src_rank, d.src_kind, d.dst_rank, d.dst_kind)
+        g = groups.setdefault(key, ([], []))
+        g[0].append(d.src_off + r * d.src_stride + c)
+        g[1].append(d.dst_off + r * d.dst_stride + c)
+    n_checked = 0
+    for (op, sr, sk, dr, dk), (so, do) in groups.items():
+        dn, di = _owners_of(spec, dst, dr, dk, np.concatenate(do))
+        if op == lv.OP_ZERO:
+            assert (dn == None).all()                            # noqa: E711 - elementwise on an object array
+            continue
+        sn, si = _owners_of(spec, src, sr, sk, np.concatenate(so))
+        assert (dn != None).all() and (sn == dn).all() and (si == di).all(), (op, sr, sk, dr, dk)   # noqa: E711
+        assert (sk == dk) or (op == lv.OP_CAST_BF16 and sk == 1 and dk == 0)
+        n_checked += dn.size
+    assert n_checked >= 32 * 20
