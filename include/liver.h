@@ -11,11 +11,11 @@
  *                       tensor is intersected; non-empty intersections become
  *                       copy descriptors (the paper's TransferTask), ordered
  *                       layer-major and cut into a stream of fixed-size staging
- *                       chunks (Section 4.6.2, Section 5: "fixed-size chunks").
- *   liver_pack          source half of Algorithm 1 (slice <- T[p.bounds]): gather
+ *                       chunks (Section 4.6.2; Section 5 gives the default chunk size).
+ *   liver_pack          source half of Algorithm 1 (cutting each task's slice): gather
  *                       the pieces of one chunk from the source shards into the
  *                       contiguous staging chunk (the wire format).
- *   liver_unpack        target half of Algorithm 1 ("assemble received chunks"):
+ *   liver_unpack        target half of Algorithm 1 (assembling the new shard):
  *                       scatter one staging chunk into the target shards, writing
  *                       straight into the pre-allocated target storage (Appendix
  *                       A.1); optionally re-derives bf16 weights from fp32.
@@ -25,7 +25,7 @@
  * All logical ranks' buffers live in the memory of ONE GPU.  The library never
  * allocates in pack / unpack / reshard, never synchronises the host with the
  * device in them, and never writes a source buffer (the old world stays intact
- * until the caller commits: Section 4.8 "Failure fallback").  Extra device
+ * until the caller commits: Section 4.8, failure fallback).  Extra device
  * memory is the caller's one staging chunk plus the plan's descriptor table
  * (bounded-memory guarantee, Appendix A.1, Theorem 1).
  *

@@ -63,8 +63,8 @@ Megatron-style mixed-parallel training, stated so a reader can check it by eye):
       holds V_p/TP rows; rows with global index >= V are padding: written +0 in
       the target, never read from the source.  Logical tensors keep V rows.
   R12 buffer-table index of a rank is tp + TP*(dp + DP*pp).
-  R13 mixture of experts (n_experts = E > 0; the paper's Appendix A.2.3 extends the
-      view "to the expert dimension"): every layer's FFN becomes a router
+  R13 mixture of experts (n_experts = E > 0; Appendix A.2.3 says the view extends
+      along the expert dimension): every layer's FFN becomes a router
       (router.w [E, H], a dense parameter replicated over TP) plus E experts with
       their own gate/up/down weights.  With expert parallelism EP (EP divides DP
       and E) DP rank d belongs to expert-parallel index d % EP and holds experts
