@@ -326,3 +326,28 @@ def test_extra_fp32_state_rides_a_one_kind_plan():
     dev = to_dev(grads)
     check_against(run_direct(plan, dev, only_used=True), want, plan, "direct")
     check_against(run_staged(plan, dev, only_used=True), want, plan, "staged")
+
+
+def test_plan_of_a_source_rank_that_contributes_nothing():
+    """Degenerate case: bf16 weights are read from DP replica 0, so a plan restricted to source replica 1 and to
+    the weights moves no data.  Its reshard writes only the target's zero padding, and packing any chunk is an
+    empty launch that leaves the staging chunk untouched."""
+    print("empty source share", flush=True)
+    spec = oracle.ModelSpec(n_layers=2, hidden=64, n_q_heads=4, n_kv_heads=4, ffn=128, vocab=128, glu=True)
+    src, dst = oracle.Layout(2, 1, 2, 128), oracle.Layout(1, 2, 2, 128)
+    s, a, b = lv_objects(spec, src, dst, kinds=(0,))
+    plan = lv.liver_plan_create(s, lv.Layout(src.tp, src.pp, src.dp, src.pad_multiple, only_dp=1), b, 4096)
+    info = lv.liver_plan_info(plan)
+    assert info.bytes_read == 0 and info.n_desc_pack == 0 and info.bytes_written == info.pad_bytes > 0
+    out = alloc_dst(plan, only_used=True)
+    lv.liver_reshard(plan, {}, out)                       # no source buffer is needed at all
+    staging = torch.full((4096,), 0x3C, dtype=torch.uint8, device="cuda")
+    for c in (0, info.n_chunks - 1):
+        lv.liver_pack(plan, c, {}, staging)
+    torch.cuda.synchronize()
+    assert (staging == 0x3C).all()
+    for (r, k), t in out.items():
+        pp = r // (dst.tp * dst.dp)
+        n_local = oracle.stage_view(spec, dst, 0, pp).n_local
+        g = t.cpu().numpy().view(np.uint16)
+        assert (g[:n_local] == 0xA5A5).all() and (g[n_local:] == 0).all(), (r, k)

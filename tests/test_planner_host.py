@@ -444,3 +444,27 @@ def test_full_size_descriptors_agree_with_ownership_formulas(name):
         assert (sk == dk) or (op == lv.OP_CAST_BF16 and sk == 1 and dk == 0)
         n_checked += dn.size
     assert n_checked >= 32 * 20
+
+
+def test_plan_of_a_source_rank_that_contributes_nothing():
+    """bf16 weights are read from DP replica 0: a plan restricted to source replica 1 and to the weights has an
+    empty pack list and a direct list of zero-padding descriptors only."""
+    spec = oracle.ModelSpec(n_layers=2, hidden=64, n_q_heads=4, n_kv_heads=4, ffn=128, vocab=128, glu=True)
+    src, dst = oracle.Layout(2, 1, 2, 128), oracle.Layout(1, 2, 2, 128)
+    s, a, b = lv_objects(spec, src, dst, kinds=(0,))
+    plan = lv.liver_plan_create(s, lv.Layout(src.tp, src.pp, src.dp, src.pad_multiple, only_dp=1), b, 4096)
+    info = lv.liver_plan_info(plan)
+    assert info.bytes_read == 0 and info.n_desc_pack == 0 and info.bytes_written == info.pad_bytes > 0
+    assert all(d.op == lv.OP_ZERO for d in descs(plan, lv.LIST_DIRECT))
+    from interp import alloc_dst
+    out, _ = alloc_dst(plan)
+    lv.liver_debug_emulate_host(plan, lv.LIST_DIRECT, 0, {}, out, None)
+    staging = np.full(4096, 0x3C, np.uint8)
+    lv.liver_debug_emulate_host(plan, lv.LIST_PACK, info.n_chunks - 1, {}, None, staging)
+    assert (staging == 0x3C).all()
+    for (r, k), g in out.items():
+        n = oracle.stage_view(spec, dst, 0, r // (dst.tp * dst.dp)).n_local
+        if k == 0:
+            assert (g[:n] == 0xA5A5).all() and (g[n:] == 0).all()
+        else:
+            assert (g.view(np.uint8) == 0xA5).all()
