@@ -175,3 +175,13 @@ def test_llama7b_layout_variants_at_full_size():
     names = ["embed.word", "lm_head.w", "final_norm.w"] + _layer(ospec, 0, ("q.w", "k.w", "v.w", "o.w", "ln1.w")) \
         + _layer(ospec, 8, ("gate.w", "down.w")) + _layer(ospec, 23, ("up.w", "o.w", "ln2.w")) + _layer(ospec, 31, ("down.w", "q.w"))
     _run(cfg, names)
+
+
+def test_llama7b_single_rank_buffers_of_27_gb():
+    """Maximum buffer sizes: the whole 7B state on ONE source rank (13.5 GB of bf16, 27 GB per fp32 kind, byte
+    offsets far beyond 2^32) split for TP2; the sampled tensors include the head at the very end of the buffers."""
+    cfg = dict(synth.CONFIGS["llama7b"], name="llama7b tp1->tp2", src=dict(tp=1, pp=1, dp=1), dst=dict(tp=2, pp=1, dp=1))
+    ospec = oracle.ModelSpec(**cfg["spec"])
+    names = ["embed.word", "final_norm.w", "lm_head.w"] + _layer(ospec, 0, ("q.w", "o.w", "ln1.w")) \
+        + _layer(ospec, 17, ("k.w", "gate.w", "down.w")) + _layer(ospec, 31, ("v.w", "o.w", "up.w", "down.w", "ln2.w"))
+    _run(cfg, names)
