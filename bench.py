@@ -162,6 +162,22 @@ def main():
         w, k = timed(lambda: scratch.copy_(big), 10, 2)
         extras["torch_copy_GBs"] = round(2 * big.numel() * big.element_size() / (k * 1e-3) / 1e9, 1)
         del scratch
+        # the plainest streaming kernels (contiguous read / fill / copy, same workgroup size, 16-byte non-temporal
+        # accesses) over the SAME source and target buffers, paired by size: what this placement gives a copy
+        pairs = list(zip(sorted(src_bufs.values(), key=lambda t: -t.numel() * t.element_size()),
+                         sorted(dst_bufs.values(), key=lambda t: -t.numel() * t.element_size())))
+        pairs = [(a, b, min(a.numel() * a.element_size(), b.numel() * b.element_size()) // 32768 * 32768) for a, b in pairs]
+        pairs = [p for p in pairs if p[2] > 0]
+        probe_bytes = sum(n for _, _, n in pairs)
+        for mode, name in ((0, "plain_read_GBs"), (1, "plain_fill_GBs"), (2, "plain_copy_GBs")):
+            best = 0.0
+            for grid in (256, 2048, 8192):
+                def probe():
+                    for a, b, n in pairs:
+                        lv.liver_debug_bandwidth_probe(mode, a, b, n, min(grid, n // 32768))
+                w, k = timed(probe, 3, 1)
+                best = max(best, (2 if mode == 2 else 1) * probe_bytes / (k * 1e-3) / 1e9)
+            extras[name] = round(best, 1)
         # staged path: pack + unpack of every chunk through one staging chunk
         staging = torch.empty(cfg["chunk_bytes"], dtype=torch.uint8, device="cuda")
         nch = info.n_chunks

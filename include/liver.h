@@ -270,6 +270,21 @@ const char* liver_strerror(int code);
 int liver_debug_emulate_host(const liver_plan_t* plan, int list, int chunk, const void* const* src_bufs,
                              void* const* dst_bufs, void* staging);
 
+/* Measurement aid, never called by the entry points above: enqueues on `hip_stream`
+ * the plainest streaming kernel of the library's launch shape (256-thread
+ * workgroups, grid-stride over 32 KiB tiles, 16-byte non-temporal accesses) over
+ * `bytes` bytes of DEVICE memory, so that a benchmark can quote what a plain
+ * read, fill or copy reaches on the same buffers the reshard uses.
+ *   mode 0  read src[0, bytes); additionally stores 16 bytes per workgroup into
+ *           dst[0, grid*16) (dst must hold at least that; grid*16 <= bytes)
+ *   mode 1  fill dst[0, bytes) with a fixed pattern (src is ignored)
+ *   mode 2  copy src[0, bytes) to dst[0, bytes)
+ * bytes: positive multiple of 32768; grid: 1..65536 workgroups; pointers 16-byte
+ * aligned, owned by the caller, not overlapping.  Asynchronous, allocates
+ * nothing.  LIVER_E_INVALID_ARG on a bad argument (nothing is launched),
+ * LIVER_E_HIP if the launch fails. */
+int liver_debug_bandwidth_probe(int mode, const void* src, void* dst, size_t bytes, int grid, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

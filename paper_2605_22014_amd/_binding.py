@@ -136,6 +136,7 @@ def _load() -> C.CDLL:
     lib.liver_reshard.argtypes = [P, C.POINTER(P), C.POINTER(P), P]
     lib.liver_reshard_staged.argtypes = [P, C.POINTER(P), C.POINTER(P), C.POINTER(P), C.c_int, P, P]
     lib.liver_debug_emulate_host.argtypes = [P, C.c_int, C.c_int, C.POINTER(P), C.POINTER(P), P]
+    lib.liver_debug_bandwidth_probe.argtypes = [C.c_int, P, P, C.c_size_t, C.c_int, P]
     lib.liver_strerror.argtypes = [C.c_int]
     lib.liver_strerror.restype = C.c_char_p
     return lib
@@ -269,6 +270,12 @@ def liver_debug_emulate_host(plan: Plan, which: int, chunk: int, src_bufs, dst_b
     _check(_lib.liver_debug_emulate_host(plan.handle, which, chunk, table(src_bufs, plan.src.n_ranks),
                                          table(dst_bufs, plan.dst.n_ranks),
                                          staging.ctypes.data if staging is not None else None))
+
+
+def liver_debug_bandwidth_probe(mode: int, src, dst, nbytes: int, grid: int, stream=None) -> None:
+    """Plain read (0) / fill (1) / copy (2) of nbytes of device memory; src, dst: tensors or addresses."""
+    _check(_lib.liver_debug_bandwidth_probe(mode, _addr(src) if src is not None else None, _addr(dst) if dst is not None else None,
+                                            nbytes, grid, _stream(stream)))
 
 
 def make_table(bufs: Dict[Tuple[int, int], object], n_ranks: int):

@@ -247,6 +247,20 @@ int liver_reshard_staged(const liver_plan_t* plan, const void* const* src_bufs, 
     return LIVER_OK;
 }
 
+int liver_debug_bandwidth_probe(int mode, const void* src, void* dst, size_t bytes, int grid, void* hip_stream) {
+    const size_t tile_bytes = (size_t)liver::PROBE_TILE_UNITS * 16;
+    if (mode < 0 || mode > 2) return fail(LIVER_E_INVALID_ARG, "probe mode must be 0 (read), 1 (fill) or 2 (copy)");
+    if (!dst || (mode != 1 && !src)) return fail(LIVER_E_INVALID_ARG, "probe buffer is NULL");
+    if ((uintptr_t)dst % 16 || (uintptr_t)src % 16) return fail(LIVER_E_INVALID_ARG, "buffers must be 16-byte aligned");
+    if (bytes == 0 || bytes % tile_bytes) return fail(LIVER_E_INVALID_ARG, "probe size must be a positive multiple of 32 KiB");
+    if (grid < 1 || grid > 65536) return fail(LIVER_E_INVALID_ARG, "probe grid must be 1..65536");
+    if (mode == 0 && (size_t)grid * 16 > bytes) return fail(LIVER_E_INVALID_ARG, "read probe needs grid*16 <= bytes");
+    const uint64_t n_tiles = bytes / tile_bytes;
+    const hipError_t e = liver::launch_probe(mode, src, dst, n_tiles, (uint32_t)grid, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(LIVER_E_HIP, std::string("probe launch: ") + hipGetErrorString(e));
+    return LIVER_OK;
+}
+
 const char* liver_strerror(int code) {
     static thread_local std::string msg;
     const char* base = "unknown error";

@@ -210,6 +210,41 @@ __global__ __launch_bounds__(BLOCK) void liver_copy_kernel(const PassArgs args) 
 
 }  // namespace
 
+// Reference dispatches for measurement: the plainest streaming kernels the chip can run (grid-stride over
+// tiles of PROBE_TILE_UNITS contiguous 16-byte units, PROBE_TILE_UNITS / BLOCK non-temporal accesses in flight per lane).
+// MODE 0 reads `a` (and stores one unit per workgroup into `b` so the loads stay), 1 fills `b`, 2 copies.
+template <int MODE>
+__global__ __launch_bounds__(BLOCK) void liver_probe_kernel(const u32x4* __restrict__ a, u32x4* __restrict__ b, uint64_t n_tiles) {
+    constexpr int U = PROBE_TILE_UNITS / BLOCK;
+    u32x4 acc = {1u, 2u, 3u, 4u};
+    for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const uint64_t at0 = t * PROBE_TILE_UNITS + threadIdx.x;
+        u32x4 v[U];
+#pragma unroll
+        for (int i = 0; i < U; ++i) v[i] = MODE == 1 ? acc : __builtin_nontemporal_load(a + at0 + (uint64_t)i * BLOCK);
+        if (MODE == 0) {
+#pragma unroll
+            for (int i = 0; i < U; ++i) acc ^= v[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < U; ++i) __builtin_nontemporal_store(v[i], b + at0 + (uint64_t)i * BLOCK);
+        }
+    }
+    if (MODE == 0 && threadIdx.x == 0) b[blockIdx.x] = acc;  // lane 0's value: enough to keep every lane's loads
+}
+
+hipError_t launch_probe(int mode, const void* src, void* dst, uint64_t n_tiles, uint32_t grid, hipStream_t stream) {
+    dim3 g(grid), b(BLOCK);
+    const u32x4* a = (const u32x4*)src;
+    u32x4* o = (u32x4*)dst;
+    switch (mode) {
+        case 0: hipLaunchKernelGGL((liver_probe_kernel<0>), g, b, 0, stream, a, o, n_tiles); break;
+        case 1: hipLaunchKernelGGL((liver_probe_kernel<1>), g, b, 0, stream, a, o, n_tiles); break;
+        default: hipLaunchKernelGGL((liver_probe_kernel<2>), g, b, 0, stream, a, o, n_tiles); break;
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_pass(const PassArgs& args, uint32_t grid, int cache_hints, hipStream_t stream) {
     if (args.n_tiles == 0 || args.n_desc == 0) return hipSuccess;
     dim3 g(grid), b(BLOCK);

@@ -23,4 +23,8 @@ static_assert(sizeof(PassArgs) <= 3584, "kernel arguments must fit the kernarg s
 // Enqueue one pass on `stream` with `grid` workgroups (1 <= grid <= n_tiles).
 hipError_t launch_pass(const PassArgs& args, uint32_t grid, int cache_hints, hipStream_t stream);
 
+// Reference dispatch (read / fill / copy of n_tiles * PROBE_TILE_UNITS contiguous 16-byte units).
+constexpr uint32_t PROBE_TILE_UNITS = 2048;  // 32 KiB per workgroup step
+hipError_t launch_probe(int mode, const void* src, void* dst, uint64_t n_tiles, uint32_t grid, hipStream_t stream);
+
 }  // namespace liver

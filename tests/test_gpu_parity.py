@@ -351,3 +351,26 @@ def test_plan_of_a_source_rank_that_contributes_nothing():
         n_local = oracle.stage_view(spec, dst, 0, pp).n_local
         g = t.cpu().numpy().view(np.uint16)
         assert (g[:n_local] == 0xA5A5).all() and (g[n_local:] == 0).all(), (r, k)
+
+
+@pytest.mark.parametrize("grid", [1, 256, 5000])
+def test_bandwidth_probe_kernels(grid):
+    """The measurement aid's plain kernels do what they say: copy copies, fill fills the whole range and
+    nothing after it, read leaves the source alone and touches only the first grid*16 bytes of dst."""
+    print(f"bandwidth probe grid {grid}", flush=True)
+    n = 37 * 32768                                            # ragged against every grid
+    g = torch.Generator(device="cuda").manual_seed(grid)
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda", generator=g)
+    keep = src.clone()
+    dst = torch.full((n + 4096,), 0x5A, dtype=torch.uint8, device="cuda")
+    lv.liver_debug_bandwidth_probe(2, src, dst, n, grid)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n], src) and (dst[n:] == 0x5A).all()
+    lv.liver_debug_bandwidth_probe(1, None, dst, n, grid)
+    torch.cuda.synchronize()
+    want = torch.tensor([1, 2, 3, 4], dtype=torch.int32, device="cuda").repeat(n // 16)
+    assert torch.equal(dst[:n].view(torch.int32), want) and (dst[n:] == 0x5A).all()
+    dst.fill_(0x5A)
+    lv.liver_debug_bandwidth_probe(0, src, dst, n, grid)
+    torch.cuda.synchronize()
+    assert torch.equal(src, keep) and (dst[min(grid, n // 16) * 16:] == 0x5A).all()
