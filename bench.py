@@ -171,7 +171,7 @@ def main():
         probe_bytes = sum(n for _, _, n in pairs)
         for mode, name in ((0, "plain_read_GBs"), (1, "plain_fill_GBs"), (2, "plain_copy_GBs")):
             best = 0.0
-            for grid in (256, 2048, 8192):
+            for grid in (256, 2048, 8192, 32768):
                 def probe():
                     for a, b, n in pairs:
                         lv.liver_debug_bandwidth_probe(mode, a, b, n, min(grid, n // 32768))
