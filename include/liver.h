@@ -186,7 +186,7 @@ typedef struct {
 } liver_desc_t;
 
 /* Plan the reshard of `spec` from world `src` to world `dst` (Section 4.6.1;
- * Algorithm 1, line 1).  Touches metadata only -- no tensor data, no data pointers.
+ * the planning step that opens Algorithm 1).  Touches metadata only -- no tensor data, no data pointers.
  * chunk_bytes: size of the caller's staging chunk, a multiple of 256, >= 256.
  * If a HIP device is present the descriptor tables are uploaded to the current
  * device (the plan's single device allocation, freed by liver_plan_destroy); if
@@ -196,7 +196,9 @@ typedef struct {
  * UNSUPPORTED (layers do not split over the stages as asked, hidden % n_q_heads, n_q_heads % n_kv_heads,
  * ffn % tp non-zero, vocab % tp non-zero without vocab_multiple, kv heads neither split (n_kv_heads % tp == 0) nor
  * replicated evenly (tp % n_kv_heads == 0 and q heads per group % (tp/n_kv_heads) == 0); only_* out of
- * range), NOMEM, HIP. */
+ * range; beyond the sanity caps: 2^16 layers, heads, experts, stages or model chunks, 2^24 for any other
+ * dimension, padding multiple or rank count; a chunk_bytes so small that the stream would have more than
+ * 2^20 chunks, or a plan of more than 2^22 transfer tasks), NOMEM, HIP. */
 int liver_plan_create(const liver_model_spec_t* spec, const liver_layout_t* src,
                       const liver_layout_t* dst, size_t chunk_bytes, liver_plan_t** out);
 

@@ -325,6 +325,8 @@ struct Builder {
     // j-th rank (in slice order) of the group that shares the buffer of expert-parallel index ep
     int group_dp(const liver_layout_t& l, int ep, int j) const { return expert ? ep + ep_of(l) * j : j; }
 
+    static constexpr size_t MAX_ENTRIES = size_t(1) << 22;
+
     void push_bounded(Entry&& e) {  // keep every entry below 2^30 elements (32-bit unit counters)
         const i64 lim = i64(1) << 30, total = e.rows * e.run;
         if (total <= lim) {
@@ -341,6 +343,7 @@ struct Builder {
         const liver_layout_t &S = plan.src, &D = plan.dst;
         const bool derive = (D.flags & LIVER_DERIVE_BF16) != 0;
         const int kb = kbase(), n_dst = group_size(D);
+        if (entries.size() > MAX_ENTRIES) return;  // plan_family reports it after this column
         if (kind_on(LIVER_PARAM_BF16) && !derive) {
             for (int j = 0; j < n_dst; ++j) {
                 const int dp = group_dp(D, d_ep, j);
@@ -436,7 +439,7 @@ struct Builder {
 
     int run();
     int plan_family();
-    void emit_lists();
+    int emit_lists();
     int lower(List& list, bool staged);
 };
 
@@ -453,6 +456,21 @@ int Builder::run() {
             l->pp_first < 0 || l->pp_last < 0 || l->bucket_elems < 0 || l->ep < 0) {
             why = "layout: tp, pp, dp, pad_multiple must be positive; vpp, vocab_multiple, pp_first, pp_last, bucket_elems, ep non-negative";
             return LIVER_E_INVALID_ARG;
+        }
+    // Sanity caps, far above any real model or cluster: they keep a garbage struct (say, uninitialised memory)
+    // from turning into hours of planning or an allocation of many gigabytes, and all products below in 64 bits.
+    constexpr int DIM_CAP = 1 << 24, COUNT_CAP = 1 << 16;
+    if (sp.n_layers > COUNT_CAP || sp.n_q_heads > COUNT_CAP || sp.n_experts > COUNT_CAP || sp.hidden > DIM_CAP ||
+        sp.ffn > DIM_CAP || sp.vocab > DIM_CAP || sp.max_pos > DIM_CAP) {
+        why = "model_spec: more than 2^16 layers, heads or experts, or a dimension above 2^24";
+        return LIVER_E_UNSUPPORTED;
+    }
+    for (const liver_layout_t* l : {&S, &D})
+        if (l->tp > DIM_CAP || l->pp > COUNT_CAP || l->dp > DIM_CAP || (i64)l->tp * l->pp > DIM_CAP ||
+            (i64)l->tp * l->pp * l->dp > DIM_CAP || l->pad_multiple > DIM_CAP || l->vocab_multiple > DIM_CAP ||
+            l->vpp > COUNT_CAP || l->ep > DIM_CAP) {
+            why = "layout: more than 2^24 ranks, 2^16 stages or model chunks, or a padding multiple above 2^24";
+            return LIVER_E_UNSUPPORTED;
         }
     if (plan.chunk_bytes < 256 || plan.chunk_bytes % 256) {
         why = "chunk_bytes must be a positive multiple of 256";
@@ -481,10 +499,6 @@ int Builder::run() {
     if (D.only_tp < -1 || D.only_tp >= D.tp || D.only_pp < -1 || D.only_pp >= D.pp || D.only_dp < -1 ||
         D.only_dp >= D.dp || (D.flags & ~1u) || (D.kind_mask & ~15u)) {
         why = "target layout: only_* out of range or unknown flag";
-        return LIVER_E_UNSUPPORTED;
-    }
-    if ((i64)S.tp * S.pp * S.dp > (i64(1) << 24) || (i64)D.tp * D.pp * D.dp > (i64(1) << 24)) {
-        why = "more than 2^24 ranks";
         return LIVER_E_UNSUPPORTED;
     }
     g.L = sp.n_layers, g.H = sp.hidden, g.nq = sp.n_q_heads, g.nkv = sp.n_kv_heads;
@@ -531,7 +545,7 @@ int Builder::run() {
         if (x.kind != y.kind) return x.kind < y.kind;
         return x.off < y.off;
     });
-    emit_lists();
+    if (int rc = emit_lists()) return rc;
     int rc = lower(plan.direct, false);
     if (rc == LIVER_OK) rc = lower(plan.pack, true);
     if (rc == LIVER_OK) rc = lower(plan.unpack, true);
@@ -641,6 +655,10 @@ int Builder::plan_family() {
             for (const Piece& p : merged)
                 expand(p.slot, p.s_tp, p.s_pp, p.s_ep, tp, pp, d_ep, p.s_off, p.s_stride, p.d_off, p.d_stride, p.rows, p.run);
             zero_padding(col, d_ep);
+            if (entries.size() > MAX_ENTRIES) {  // sanity cap; the 175B model on 1024 ranks needs ~10^5
+                why = "the plan would have more than 2^22 transfer tasks";
+                return LIVER_E_UNSUPPORTED;
+            }
         }
     }
     return LIVER_OK;
@@ -648,8 +666,17 @@ int Builder::plan_family() {
 
 // Direct list: one descriptor per (entry, destination).  Staged lists: walk the
 // entries in stream order, give each its place on the wire, split at chunk ends.
-void Builder::emit_lists() {
+int Builder::emit_lists() {
     const i64 B = (i64)plan.chunk_bytes;
+    {   // every chunk costs descriptors and a launch: refuse a staging chunk that is absurdly small for this state
+        i64 wire = 0;
+        for (const Entry& e : entries)
+            if (e.src_rank >= 0) wire += e.rows * e.run * elem_bytes(e.src_kind) + 16;
+        if (wire / B >= (i64(1) << 20)) {
+            why = "chunk_bytes is too small for this state: the stream would have more than 2^20 chunks";
+            return LIVER_E_UNSUPPORTED;
+        }
+    }
     auto pub = [](const Entry& e, const Dst& d, int chunk) {
         liver_desc_t o{};
         o.op = d.op, o.chunk = chunk, o.slot = e.slot;
@@ -707,6 +734,7 @@ void Builder::emit_lists() {
     // chunk order (the unpack list can hold zero fills slightly out of order)
     auto by_chunk = [](const liver_desc_t& a, const liver_desc_t& b) { return a.chunk < b.chunk; };
     std::stable_sort(plan.unpack.pub.begin(), plan.unpack.pub.end(), by_chunk);
+    return LIVER_OK;
 }
 
 // Turn public descriptors into device descriptors, grouped into launches.

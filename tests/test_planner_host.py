@@ -479,3 +479,50 @@ def test_bandwidth_probe_rejects_bad_arguments_before_any_launch():
         with pytest.raises(lv.LiverError) as e:
             lv.liver_debug_bandwidth_probe(kw["mode"], kw["src"], kw["dst"], kw["nbytes"], kw["grid"], stream=0)
         assert e.value.code == -1, bad
+
+
+def test_garbage_structs_are_rejected_quickly():
+    """Structs filled with arbitrary integers (uninitialised memory, say) come back as an error or a small valid
+    plan, never as a crash, a long planning run or a huge allocation."""
+    import time
+    from paper_2605_22014_amd import _binding as B
+    rng = np.random.default_rng(2014)
+    pool = [0, -1, 1, 2, 3, 4, 8, 64, 96, 128, 1 << 15, 1 << 20, (1 << 24) + 1, (1 << 31) - 1, -(1 << 31)]
+    t0, n_ok, n_err = time.perf_counter(), 0, 0
+    for case in range(300):
+        pick = lambda: int(pool[rng.integers(len(pool))])
+        s = B._Spec(*[pick() for _ in range(7)], pick() & 0xFFFFFFFF, pick())
+        lays = []
+        for _ in range(2):
+            lays.append(B._Layout(*[pick() for _ in range(7)], pick() & 0xFFFFFFFF, pick() & 0xFFFFFFFF,
+                                            pick(), pick(), pick(), pick(), pick(), pick()))
+        handle = ctypes.c_void_p()
+        rc = B._lib.liver_plan_create(ctypes.byref(s), ctypes.byref(lays[0]), ctypes.byref(lays[1]),
+                                                ctypes.c_size_t(256 * max(1, pick() & 0xFFFF)), ctypes.byref(handle))
+        if rc == 0:
+            n_ok += 1
+            B._lib.liver_plan_destroy(handle)
+        else:
+            n_err += 1
+            assert rc in (-1, -2), (case, rc)
+    assert n_err > 250 and time.perf_counter() - t0 < 60
+    # one garbage field in an otherwise valid request reaches the deeper checks
+    good_spec = dict(n_layers=4, hidden=64, n_q_heads=8, n_kv_heads=4, ffn=96, vocab=128, max_pos=16, flags=15, n_experts=0)
+    good_lay = dict(tp=2, pp=2, dp=2, pad_multiple=8, only_tp=-1, only_pp=-1, only_dp=-1, flags=0, kind_mask=0, vpp=1,
+                    vocab_multiple=0, pp_first=0, pp_last=0, bucket_elems=0, ep=1)
+    n_ok = 0
+    for case in range(600):
+        sp, a, b = dict(good_spec), dict(good_lay), dict(good_lay, tp=4, pp=1, dp=3)
+        target = (sp, a, b)[case % 3]
+        field = list(target)[rng.integers(len(target))]
+        v = int(pool[rng.integers(len(pool))])
+        target[field] = v & 0xFFFFFFFF if field in ("flags", "kind_mask") else v
+        handle = ctypes.c_void_p()
+        rc = B._lib.liver_plan_create(ctypes.byref(B._Spec(**sp)), ctypes.byref(B._Layout(**a)), ctypes.byref(B._Layout(**b)),
+                                      ctypes.c_size_t(4096), ctypes.byref(handle))
+        assert rc in (0, -1, -2), (case, field, v, rc)
+        if rc == 0:
+            n_ok += 1
+            assert B._lib.liver_plan_desc_count(handle, 0) < 1_000_000, (field, v)
+            B._lib.liver_plan_destroy(handle)
+    assert 50 < n_ok < 550 and time.perf_counter() - t0 < 120
