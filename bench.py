@@ -237,7 +237,7 @@ def _column_used(lv, plan, src, rank):
     return any(lv.liver_plan_buffer_used(plan, 0, src.rank(tp, pp, d), k) for d in range(src.dp) for k in range(4))
 
 
-def cpu_baseline(cfg, src_bufs, dst_bufs, src, dst, n_layers_sampled=8):
+def cpu_baseline(cfg, src_bufs, dst_bufs, src, dst, n_layers_sampled=12):
     """The CPU oracle (gather to full logical tensors, re-split) timed on a bounded
     sample of the same workload: all tensors of a few transformer layers spread
     over the model (of the planned target stage for a filtered plan), all buffer
