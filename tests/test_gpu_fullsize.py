@@ -185,3 +185,37 @@ def test_llama7b_single_rank_buffers_of_27_gb():
     names = ["embed.word", "final_norm.w", "lm_head.w"] + _layer(ospec, 0, ("q.w", "o.w", "ln1.w")) \
         + _layer(ospec, 17, ("k.w", "gate.w", "down.w")) + _layer(ospec, 31, ("v.w", "o.w", "up.w", "down.w", "ln2.w"))
     _run(cfg, names)
+
+
+def _digest(bufs):
+    """Order-sensitive digest of every buffer: plain sum and position-weighted sum of the raw words."""
+    out = {}
+    for key, t in bufs.items():
+        v = t.view(torch.int16 if key[1] == 0 else torch.int32)
+        w = torch.arange(v.numel(), device=v.device, dtype=torch.int64) % 65521 + 1
+        out[key] = (int(v.sum(dtype=torch.int64)), int((w * v).sum(dtype=torch.int64)))
+        del w
+    return out
+
+
+def test_llama7b_every_launch_shape_gives_the_same_bits():
+    """Full 7B size (1.44 M tiles in one pass): grids from one workgroup per CU to 65536, the three tile orders
+    and the four cache-hint settings all reproduce the digest of the default launch, which the sampled oracle
+    comparison has verified in the same run."""
+    _, ospec, _, _ = cfg_objects("llama7b")
+    print("llama7b launch shapes: generating state in HBM", flush=True)
+    cfg, only, ospec, osrc, odst, plan, src, dst, src_bufs = _setup("llama7b")
+    dst_bufs = _fresh_dst(plan, dst)
+    lv.liver_reshard(plan, src_bufs, dst_bufs)
+    torch.cuda.synchronize()
+    names = ["lm_head.w"] + _layer(ospec, 0, ("o.w", "gate.w")) + _layer(ospec, 31, ("q.w", "down.w"))
+    _compare(_expected(cfg, only, ospec, osrc, odst, src_bufs, names), only, odst, dst_bufs, "default launch")
+    want = _digest(dst_bufs)
+    for grid, order, hints in [(256, 1, 3), (512, 0, 0), (1000, 2, 1), (4096, 1, 2), (65536, 0, 3), (65536, 2, 0), (97, 2, 3)]:
+        print(f"llama7b launch shapes: grid {grid} order {order} hints {hints}", flush=True)
+        for t in dst_bufs.values():
+            t.fill_(-23131 if t.dtype == torch.int16 else -1515870811)
+        lv.liver_plan_set_launch(plan, grid, order, hints)
+        lv.liver_reshard(plan, src_bufs, dst_bufs)
+        torch.cuda.synchronize()
+        assert _digest(dst_bufs) == want, (grid, order, hints)
