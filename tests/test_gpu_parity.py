@@ -124,6 +124,18 @@ def test_gpt2_small_direct_and_staged(gpt2):
     check_against(run_staged(plan, dev), want, plan, "staged 64 MiB")
 
 
+@pytest.mark.parametrize("seed", [synth.SEED_BASE + 1, synth.SEED_BASE + 2])
+def test_gpt2_small_other_seeds(seed):
+    cfg, spec, src, dst = cfg_objects("gpt2_small")
+    print(f"gpt2_small seed {seed}", flush=True)
+    world = make_world(spec, src, synth.logical_state(oracle.logical_tensors(spec), seed, cfg["dist"]))
+    want = oracle.reshard_state(spec, src, dst, world)
+    plan = _plan(spec, src, dst, cfg["chunk_bytes"])
+    dev = to_dev(world)
+    check_against(run_direct(plan, dev), want, plan, "direct")
+    check_against(run_staged(plan, dev), want, plan, "staged 64 MiB")
+
+
 def test_gpt2_small_derive(gpt2):
     cfg, spec, src, dst, world, want, dev = gpt2
     print("gpt2_small derive", flush=True)
