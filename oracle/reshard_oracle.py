@@ -10,8 +10,8 @@ What the paper fixes (LiveR, Section 4.6 and Appendix A.2):
   * a reshard is correct iff the union of all shards is the same before and
     after (Appendix A.2.1, Eq. 1) and every element of the global state appears
     exactly once in the new configuration (Section 4.6, constraint 1);
-  * the paper's own check is "aggregate the global tensors and compare
-    element-wise" with deviation exactly zero (Section 6.6).
+  * the paper's own check gathers the global tensors before and after and
+    compares them element by element, with deviation exactly zero (Section 6.6).
 So the result has a plain definition: gather, then split.  This file writes that
 definition out.
 
