@@ -115,7 +115,7 @@ def main():
         for d in range(1, src.dp):
             src_bufs[(src.rank(tp, pp, d), lv.PARAM)].copy_(col["param"])
     from paper_2605_22014_amd._binding import make_table
-    src_tab, dst_tab = make_table(src_bufs, src.n_ranks), make_table(dst_bufs, dst.n_ranks)
+    src_tab, dst_tab = make_table(src_bufs, src.n_ranks, plan, 0), make_table(dst_bufs, dst.n_ranks, plan, 1)
     torch.cuda.synchronize()
 
     def timed(fn, steps, warmup):

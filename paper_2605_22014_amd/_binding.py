@@ -159,6 +159,13 @@ class Plan:
 
     def __init__(self, handle: int, src: Layout, dst: Layout, chunk_bytes: int):
         self.handle, self.src, self.dst, self.chunk_bytes = handle, src, dst, chunk_bytes
+        self._sizes = {}
+
+    def _buffer_bytes(self, side: int, rank: int, kind: int) -> int:
+        key = (side, rank, kind)
+        if key not in self._sizes:
+            self._sizes[key] = liver_plan_buffer_bytes(self, side, rank, kind)
+        return self._sizes[key]
 
     def __del__(self):
         try:
@@ -224,13 +231,29 @@ def _addr(x) -> int:
     return x.data_ptr()          # torch tensor (device memory)
 
 
-def _table(bufs, n_ranks: int):
-    """{(rank, kind): tensor | address} -> void*[n_ranks*NUM_KINDS]."""
+def _checked(t, need: int, what: str) -> int:
+    """Address of a device tensor after checking what a raw pointer cannot tell the library: that it is device
+    memory, contiguous and at least `need` bytes long (a short buffer would be a GPU memory fault)."""
+    if t is None or isinstance(t, int):
+        return _addr(t)           # raw address: the caller vouches for it, as through the C ABI
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{what}: must be a contiguous device tensor")
+    have = t.numel() * t.element_size()
+    if have < need:
+        raise ValueError(f"{what}: {have} bytes, the plan needs {need}")
+    return t.data_ptr()
+
+
+def _table(bufs, n_ranks: int, plan: "Plan" = None, side: int = 0):
+    """{(rank, kind): tensor | address} -> void*[n_ranks*NUM_KINDS]; tensors are size-checked against the plan."""
     if not isinstance(bufs, dict):
         return bufs               # already a ctypes array
     arr = (C.c_void_p * (n_ranks * NUM_KINDS))()
     for (rank, kind), t in bufs.items():
-        arr[rank * NUM_KINDS + kind] = _addr(t)
+        if not (0 <= rank < n_ranks and 0 <= kind < NUM_KINDS):
+            raise ValueError(f"buffer key {(rank, kind)} out of range")
+        need = plan._buffer_bytes(side, rank, kind) if plan is not None else 0
+        arr[rank * NUM_KINDS + kind] = _checked(t, need, f"{'target' if side else 'source'} buffer {(rank, kind)}")
     return arr
 
 
@@ -241,22 +264,25 @@ def _stream(stream) -> int:
 
 
 def liver_pack(plan: Plan, chunk: int, src_bufs, staging, stream=None) -> None:
-    _check(_lib.liver_pack(plan.handle, chunk, _table(src_bufs, plan.src.n_ranks), _addr(staging), _stream(stream)))
+    _check(_lib.liver_pack(plan.handle, chunk, _table(src_bufs, plan.src.n_ranks, plan, 0),
+                           _checked(staging, plan.chunk_bytes, "staging chunk"), _stream(stream)))
 
 
 def liver_unpack(plan: Plan, chunk: int, staging, dst_bufs, stream=None) -> None:
-    _check(_lib.liver_unpack(plan.handle, chunk, _addr(staging), _table(dst_bufs, plan.dst.n_ranks), _stream(stream)))
+    _check(_lib.liver_unpack(plan.handle, chunk, _checked(staging, plan.chunk_bytes, "staging chunk"),
+                             _table(dst_bufs, plan.dst.n_ranks, plan, 1), _stream(stream)))
 
 
 def liver_reshard(plan: Plan, src_bufs, dst_bufs, stream=None) -> None:
-    _check(_lib.liver_reshard(plan.handle, _table(src_bufs, plan.src.n_ranks), _table(dst_bufs, plan.dst.n_ranks),
-                              _stream(stream)))
+    _check(_lib.liver_reshard(plan.handle, _table(src_bufs, plan.src.n_ranks, plan, 0),
+                              _table(dst_bufs, plan.dst.n_ranks, plan, 1), _stream(stream)))
 
 
 def liver_reshard_staged(plan: Plan, src_bufs, dst_bufs, staging, stream_pack=None, stream_unpack=None) -> None:
     """staging: list of device chunks (tensors or addresses) of chunk_bytes each."""
-    arr = (C.c_void_p * len(staging))(*[_addr(t) for t in staging])
-    _check(_lib.liver_reshard_staged(plan.handle, _table(src_bufs, plan.src.n_ranks), _table(dst_bufs, plan.dst.n_ranks),
+    arr = (C.c_void_p * len(staging))(*[_checked(t, plan.chunk_bytes, "staging chunk") for t in staging])
+    _check(_lib.liver_reshard_staged(plan.handle, _table(src_bufs, plan.src.n_ranks, plan, 0),
+                                     _table(dst_bufs, plan.dst.n_ranks, plan, 1),
                                      arr, len(staging), _stream(stream_pack), _stream(stream_unpack)))
 
 
@@ -278,6 +304,6 @@ def liver_debug_bandwidth_probe(mode: int, src, dst, nbytes: int, grid: int, str
                                             nbytes, grid, _stream(stream)))
 
 
-def make_table(bufs: Dict[Tuple[int, int], object], n_ranks: int):
-    """Marshal a buffer dictionary once, for repeated calls."""
-    return _table(bufs, n_ranks)
+def make_table(bufs: Dict[Tuple[int, int], object], n_ranks: int, plan: Plan = None, side: int = 0):
+    """Marshal a buffer dictionary once, for repeated calls (size-checked if the plan and its side are given)."""
+    return _table(bufs, n_ranks, plan, side)

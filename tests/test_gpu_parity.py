@@ -172,6 +172,34 @@ def test_errors_on_device():
         assert torch.equal(keep[k], dst_bufs[k])
 
 
+def test_binding_rejects_short_or_host_buffers_before_any_launch():
+    """A raw pointer cannot tell the library how long a buffer is; the Python binding can, and refuses a tensor
+    that is too short, on the host or not contiguous instead of letting a kernel fault."""
+    cfg, spec, src, dst = cfg_objects("tiny_gpt")
+    world = make_world(spec, src, synth.logical_state(oracle.logical_tensors(spec), 5, "uniform"))
+    plan = _plan(spec, src, dst, 1 << 20)
+    dev, dst_bufs = to_dev(world), alloc_dst(plan)
+    keep = {k: t.clone() for k, t in dst_bufs.items()}
+    staging = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    key = (0, lv.MASTER)
+    with pytest.raises(ValueError, match="the plan needs"):
+        lv.liver_reshard(plan, dev, dict(dst_bufs, **{key: dst_bufs[key][:-1]}))
+    with pytest.raises(ValueError, match="the plan needs"):
+        lv.liver_reshard(plan, dict(dev, **{key: dev[key][: dev[key].numel() // 2]}), dst_bufs)
+    with pytest.raises(ValueError, match="device tensor"):
+        lv.liver_reshard(plan, dict(dev, **{key: dev[key].cpu()}), dst_bufs)
+    with pytest.raises(ValueError, match="device tensor"):
+        lv.liver_reshard(plan, dev, dict(dst_bufs, **{key: torch.empty(2 * dst_bufs[key].numel(), dtype=torch.int32, device="cuda")[::2]}))
+    with pytest.raises(ValueError, match="staging"):
+        lv.liver_pack(plan, 0, dev, staging[: 1 << 19])
+    with pytest.raises(ValueError, match="out of range"):
+        lv.liver_reshard(plan, dict(dev, **{(src.tp * src.pp * src.dp, 0): dev[key]}), dst_bufs)
+    torch.cuda.synchronize()
+    for k in keep:
+        assert torch.equal(keep[k], dst_bufs[k])
+    check_against(run_direct(plan, dev), oracle.reshard_state(spec, src, dst, world), plan, "direct after the refusals")
+
+
 @pytest.mark.parametrize("n_staging,two_streams", [(1, False), (2, True), (3, True), (2, False)])
 def test_pipelined_staged_reshard(gpt2, n_staging, two_streams):
     """liver_reshard_staged: pack(k+1) overlaps unpack(k) through n_staging chunks."""
