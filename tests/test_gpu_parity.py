@@ -183,17 +183,17 @@ def test_binding_rejects_short_or_host_buffers_before_any_launch():
     staging = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
     key = (0, lv.MASTER)
     with pytest.raises(ValueError, match="the plan needs"):
-        lv.liver_reshard(plan, dev, dict(dst_bufs, **{key: dst_bufs[key][:-1]}))
+        lv.liver_reshard(plan, dev, {**dst_bufs, key: dst_bufs[key][:-1]})
     with pytest.raises(ValueError, match="the plan needs"):
-        lv.liver_reshard(plan, dict(dev, **{key: dev[key][: dev[key].numel() // 2]}), dst_bufs)
+        lv.liver_reshard(plan, {**dev, key: dev[key][: dev[key].numel() // 2]}, dst_bufs)
     with pytest.raises(ValueError, match="device tensor"):
-        lv.liver_reshard(plan, dict(dev, **{key: dev[key].cpu()}), dst_bufs)
+        lv.liver_reshard(plan, {**dev, key: dev[key].cpu()}, dst_bufs)
     with pytest.raises(ValueError, match="device tensor"):
-        lv.liver_reshard(plan, dev, dict(dst_bufs, **{key: torch.empty(2 * dst_bufs[key].numel(), dtype=torch.int32, device="cuda")[::2]}))
+        lv.liver_reshard(plan, dev, {**dst_bufs, key: torch.empty(2 * dst_bufs[key].numel(), dtype=torch.int32, device="cuda")[::2]})
     with pytest.raises(ValueError, match="staging"):
         lv.liver_pack(plan, 0, dev, staging[: 1 << 19])
     with pytest.raises(ValueError, match="out of range"):
-        lv.liver_reshard(plan, dict(dev, **{(src.tp * src.pp * src.dp, 0): dev[key]}), dst_bufs)
+        lv.liver_reshard(plan, {**dev, (src.tp * src.pp * src.dp, 0): dev[key]}, dst_bufs)
     torch.cuda.synchronize()
     for k in keep:
         assert torch.equal(keep[k], dst_bufs[k])
