@@ -414,3 +414,43 @@ def test_bandwidth_probe_kernels(grid):
     lv.liver_debug_bandwidth_probe(0, src, dst, n, grid)
     torch.cuda.synchronize()
     assert torch.equal(src, keep) and (dst[min(grid, n // 16) * 16:] == 0x5A).all()
+
+
+def test_fused_cast_on_all_2_32_bit_patterns():
+    """Exhaustive: every fp32 bit pattern goes through the fused copy + cast of the derive path (identity layout of
+    the GPT-2-small shape, 124 M elements per round).  Non-NaN results must equal torch's device conversion, NaN
+    results the stated rule (sign and upper payload kept, quiet bit set); the two NaN ranges and their
+    neighbourhoods are also compared with the oracle's rne_bf16; the fp32 copy must be unchanged."""
+    cfg, spec, _, _ = cfg_objects("gpt2_small")
+    lay = oracle.Layout(1, 1, 1, 128)
+    plan = _plan(spec, lay, lay, 64 << 20, derive=True, kinds=(0, 1))
+    n_local = oracle.stage_view(spec, lay, 0, 0).n_local
+    n = lv.liver_plan_buffer_bytes(plan, 0, 0, lv.MASTER) // 4
+    master = torch.zeros(n, dtype=torch.int32, device="cuda")
+    out = alloc_dst(plan, only_used=True)
+    assert set(out) == {(0, 0), (0, 1)}
+    cast_only = _plan(spec, lay, lay, 64 << 20, derive=True, kinds=(0,))
+    out2 = alloc_dst(cast_only, only_used=True)
+    idx = torch.arange(n_local, dtype=torch.int64, device="cuda")
+    oracle_checked = 0
+    for base in range(0, 1 << 32, n_local):
+        u = (idx + base) & 0xFFFFFFFF
+        master[:n_local] = torch.where(u >= (1 << 31), u - (1 << 32), u).to(torch.int32)
+        lv.liver_reshard(plan, {(0, 1): master}, out)
+        got = out[(0, 0)][:n_local].to(torch.int64) & 0xFFFF
+        f = master[:n_local].view(torch.float32)
+        nan = f != f
+        want = torch.where(nan, (u >> 16) | 0x40, f.to(torch.bfloat16).view(torch.int16).to(torch.int64) & 0xFFFF)
+        bad = (got != want).nonzero()
+        assert bad.numel() == 0, (hex(base), [hex(int(u[i])) for i in bad[:4].flatten()])
+        assert torch.equal(out[(0, 1)][:n_local], master[:n_local])
+        lv.liver_reshard(cast_only, {(0, 1): master}, out2)     # the cast without the fp32 copy
+        assert torch.equal(out2[(0, 0)][:n_local], out[(0, 0)][:n_local])
+        for lo in (0x7F7F0000, 0xFF7F0000):                     # largest finite values, infinity, every NaN above them
+            a, b = max(lo, base), min(lo + 0x00810000, base + n_local, 1 << 32)
+            if a < b:
+                bits = np.arange(a, b, dtype=np.uint64).astype(np.uint32)
+                assert np.array_equal(got[a - base:b - base].cpu().numpy().astype(np.uint16), oracle.rne_bf16(bits))
+                oracle_checked += b - a
+    assert oracle_checked == 2 * 0x00810000
+    print("all 2^32 patterns ok", flush=True)
