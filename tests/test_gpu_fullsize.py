@@ -222,8 +222,11 @@ def test_llama7b_every_launch_shape_gives_the_same_bits():
 
 
 def test_llama7b_round_trip_returns_every_bit():
-    """A -> B -> A at the full 7B size (fp32 kinds, 81 GB per world; the third world would not fit with the
-    bf16 weights as well): every source buffer comes back bit for bit.  A property that needs no oracle."""
+    """A -> B -> A at the full 7B size (fp32 kinds, 81 GB per world; a third world with the bf16 weights as well
+    would not fit).  The generated state has DIFFERENT values in the TP replicas of the norm weights, and a
+    gather reads replica 0, so: every buffer of TP rank 0 comes back bit for bit, the other ranks differ from
+    the original in at most the 65 replicated vectors, and from then on the state is a fixed point: a second
+    forward pass reproduces B exactly, and the staged path gives the same bits as the direct one."""
     cfg = dict(synth.CONFIGS["llama7b"], kinds=(1, 2, 3))
     spec = lv.ModelSpec(**cfg["spec"])
     a = dict(pad_multiple=cfg["pad_multiple"], **cfg["src"])
@@ -246,14 +249,17 @@ def test_llama7b_round_trip_returns_every_bit():
     lv.liver_reshard(back, B, A2)
     torch.cuda.synchronize()
     assert set(A2) == set(A)
-    for key in A:
-        assert torch.equal(A[key], A2[key]), key
-    del A2
-    A3 = _fresh_dst(back, back.dst)                      # and through the staged path on the way back
+    replicated = (2 * spec.n_layers + 1) * spec.hidden         # ln1.w, ln2.w per layer, final_norm.w
+    for (r, k), t in A.items():
+        differ = int((t != A2[(r, k)]).sum())
+        assert differ == 0 if r == 0 else 0 < differ <= replicated, (r, k, differ)
+    del A, t
+    print("round trip: second forward pass, staged", flush=True)
+    B2 = _fresh_dst(fwd, fwd.dst)
     staging = torch.empty(cfg["chunk_bytes"], dtype=torch.uint8, device="cuda")
-    for c in range(lv.liver_plan_info(back).n_chunks):
-        lv.liver_pack(back, c, B, staging)
-        lv.liver_unpack(back, c, staging, A3)
+    for c in range(lv.liver_plan_info(fwd).n_chunks):
+        lv.liver_pack(fwd, c, A2, staging)
+        lv.liver_unpack(fwd, c, staging, B2)
     torch.cuda.synchronize()
-    for key in A:
-        assert torch.equal(A[key], A3[key]), key
+    for key in B:
+        assert torch.equal(B[key], B2[key]), key
