@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM traffic (GB) per direct-reshard launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled
-# by what the same counters read for a plain 1 GiB copy (FETCH x1.99991, WRITE x1.0).
+# by what the same counters read for a plain 1 GiB copy (FETCH x1.99993, WRITE x1.0).
 MEASURED_TRAFFIC_GB = {"llama7b": 188.73}   # profiles/liver_copy_kernel_llama7b_direct.md
 
 
