@@ -1,8 +1,9 @@
 // Descriptor-driven copy kernels for gfx950 (CDNA4, wave64).
 //
-// One kernel serves pack, unpack and the direct reshard (LiveR, Algorithm 1:
-// "slice <- T[p.bounds]" and "assemble received chunks into T'"; Section 4.6.2):
-// each is a list of strided 2-D pieces "rows x run, A -> B".  The work is pure
+// One kernel serves pack, unpack and the direct reshard (LiveR, Section 4.6.2 and
+// Algorithm 1: the sender cuts each task's slice out of its shard, the receiver
+// assembles the slices into the new shard): each of the three is a list of
+// strided 2-D pieces, rows x run, A -> B.  The work is pure
 // HBM streaming, so the design is about memory, not arithmetic:
 //   * a piece is cut into tiles of TILE_UNITS 16-byte units (64 KiB); a tile is
 //     what one workgroup moves at a time, so 256 compute units stay evenly loaded

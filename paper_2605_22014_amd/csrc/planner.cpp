@@ -86,6 +86,9 @@ std::vector<i64> stage_layers(i64 L, const liver_layout_t& lay, int pp) {
 
 inline int ep_of(const liver_layout_t& l) { return l.ep > 1 ? l.ep : 1; }
 
+// The view function of one rank column (Section 4.6.1; Appendix A.2.2 defines a rank's view as the index
+// region of each logical tensor that it holds; Appendix A.2.3 instantiates it for TP, PP and the expert
+// dimension): every rectangle of a logical tensor the column holds, with its offset in the column's flat buffer.
 // ep < 0: the dense buffer of rank column (tp, pp).  ep >= 0: the expert buffer held by the ranks of
 // expert-parallel index ep (mixture-of-experts models only).
 Column build_column(const Geo& g, const liver_layout_t& lay, int tp, int pp, int ep = -1) {
@@ -337,7 +340,9 @@ struct Builder {
     }
 
     // One intersection piece in flat coordinates of columns (s_tp,s_pp) -> (d_tp,d_pp):
-    // expand it per buffer kind, clipping the fp32 kinds at the DP slice boundaries.
+    // expand it per buffer kind, clipping the fp32 kinds at the DP slice boundaries.  The DP rules of
+    // Appendix A.2.3 fall out here: a replicated kind is read from one replica and written to every
+    // planned target replica (growing DP copies, shrinking DP drops copies).
     void expand(int slot, int s_tp, int s_pp, int s_ep, int d_tp, int d_pp, int d_ep, i64 s_off, i64 s_stride,
                 i64 d_off, i64 d_stride, i64 rows, i64 run) {
         const liver_layout_t &S = plan.src, &D = plan.dst;
@@ -576,7 +581,9 @@ int Builder::run() {
     return LIVER_OK;
 }
 
-// Views, intersections and entries of one buffer family (`expert` selects it).
+// Views, intersections and entries of one buffer family (`expert` selects it).  Appendix A.2.2: a task is a
+// non-empty intersection of a source and a target view of the same tensor; views of different tensors
+// never meet, which is the pruning that keeps planning linear in the number of tensors.
 int Builder::plan_family() {
     const liver_layout_t &S = plan.src, &D = plan.dst;
     const int n_tensors = T_GLOBALS + (int)g.L * T_PER_LAYER + (int)(g.L * g.E) * X_PER_EXPERT;
@@ -665,7 +672,9 @@ int Builder::plan_family() {
 }
 
 // Direct list: one descriptor per (entry, destination).  Staged lists: walk the
-// entries in stream order, give each its place on the wire, split at chunk ends.
+// entries in stream order, give each its place on the wire, split at chunk ends
+// (Section 4.6.2 and Appendix A.2.4: the state streams through one staging buffer of
+// fixed size B, so at most B bytes are in flight whatever the model size; Appendix A.1).
 int Builder::emit_lists() {
     const i64 B = (i64)plan.chunk_bytes;
     {   // every chunk costs descriptors and a launch: refuse a staging chunk that is absurdly small for this state
