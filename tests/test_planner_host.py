@@ -526,3 +526,28 @@ def test_garbage_structs_are_rejected_quickly():
             assert B._lib.liver_plan_desc_count(handle, 0) < 1_000_000, (field, v)
             B._lib.liver_plan_destroy(handle)
     assert 50 < n_ok < 550 and time.perf_counter() - t0 < 120
+
+
+@pytest.mark.parametrize("chunk_bytes", [256, 1024, 1 << 20])
+def test_every_task_starts_16_byte_aligned_on_the_wire(chunk_bytes):
+    """Wire format: tasks follow each other in the order of the direct list, each starting at the next multiple
+    of 16 bytes (a no-op at real shapes, where every task is a multiple of 16 bytes long).  For an odd toy
+    model that fixes stream_bytes, which must exceed the tightly packed size."""
+    spec = ODD
+    src, dst = oracle.Layout(2, 1, 2, 1), oracle.Layout(1, 2, 3, 1)
+    s, a, b = lv_objects(spec, src, dst)
+    plan = lv.liver_plan_create(s, a, b, chunk_bytes)
+    pos = tight = 0
+    for d in descs(plan, lv.LIST_DIRECT):
+        if d.op == lv.OP_ZERO:
+            continue
+        n = d.rows * d.run * (2 if d.src_kind == 0 else 4)
+        pos = (pos + 15) // 16 * 16 + n
+        tight += n
+    info = lv.liver_plan_info(plan)
+    assert info.stream_bytes == pos > tight
+    assert info.n_chunks == -(-pos // chunk_bytes)
+    first_of_chunk = {}
+    for d in descs(plan, lv.LIST_PACK):                       # a chunk's first piece sits at its start
+        first_of_chunk.setdefault(d.chunk, d.dst_off)
+    assert set(first_of_chunk.values()) == {0}
