@@ -551,3 +551,34 @@ def test_every_task_starts_16_byte_aligned_on_the_wire(chunk_bytes):
     for d in descs(plan, lv.LIST_PACK):                       # a chunk's first piece sits at its start
         first_of_chunk.setdefault(d.chunk, d.dst_off)
     assert set(first_of_chunk.values()) == {0}
+
+
+@pytest.mark.parametrize("name", ["tiny_gpt", "gpt2_small", "llama7b"])
+def test_stream_is_layer_major(name):
+    """Section 4.6.2 / Algorithm 1: the state streams layer by layer.  Slot 0 (embeddings) comes first, then
+    slot 1 + l for layer l in ascending order, then the final norm and head; inside a slot the tasks are ordered
+    by target rank, kind and target offset.  Chunks follow the same order, so chunk k never holds an earlier
+    layer than chunk k - 1."""
+    cfg, spec, src, dst = cfg_objects(name)
+    s, a, b = lv_objects(spec, src, dst)
+    plan = lv.liver_plan_create(s, a, b, cfg["chunk_bytes"])
+    direct = descs(plan, lv.LIST_DIRECT)
+    keys = [(d.slot, d.dst_rank, d.dst_kind, d.dst_off) for d in direct]
+    assert keys == sorted(keys)
+    assert {d.slot for d in direct} == set(range(spec.n_layers + 2))
+    # the slot of a task is the layer of the target parameter it fills (the oracle's view of the target rank)
+    by_rank = {}
+    for d in direct:
+        if d.op == lv.OP_ZERO or d.dst_kind != 0:
+            continue
+        tp, pp = d.dst_rank % dst.tp, d.dst_rank // (dst.tp * dst.dp)
+        sv = by_rank.setdefault((tp, pp), oracle.stage_view(spec, dst, tp, pp))
+        prm = next(p for p in sv.params if p.offset <= d.dst_off < p.offset + p.size)
+        if prm.name.startswith("L"):
+            want = 1 + int(prm.name.split(".")[0][1:])
+        else:
+            want = 0 if prm.name in ("embed.word", "embed.pos") else spec.n_layers + 1
+        assert d.slot == want, (prm.name, d.slot)
+    for which in (lv.LIST_PACK, lv.LIST_UNPACK):
+        seq = [(d.chunk, d.slot) for d in descs(plan, which) if d.op != lv.OP_ZERO]
+        assert seq == sorted(seq)
