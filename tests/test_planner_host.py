@@ -351,7 +351,7 @@ def test_source_side_restriction_partitions_the_work():
         assert np.array_equal(out[key], want[key]) and (counts[key] == 1).all(), key
 
 
-@pytest.mark.parametrize("kw", [dict(only_dp=3), dict(only_tp=1, only_dp=0), dict(kinds=(1, 2)), dict(only_pp=1, kinds=(0,))])
+@pytest.mark.parametrize("kw", [dict(only_dp=3), dict(only_dp=2), dict(only_tp=1, only_dp=0), dict(kinds=(1, 2)), dict(only_pp=1, kinds=(0,))])
 @pytest.mark.parametrize("derive", [False, True])
 def test_filtered_plans_mixture_of_experts(kw, derive):
     """Restricted plans of an MoE model: only_dp = 3 with EP 2 plans the expert buffers of index 1 only."""
@@ -582,3 +582,40 @@ def test_stream_is_layer_major(name):
     for which in (lv.LIST_PACK, lv.LIST_UNPACK):
         seq = [(d.chunk, d.slot) for d in descs(plan, which) if d.op != lv.OP_ZERO]
         assert seq == sorted(seq)
+
+
+def test_planner_and_oracle_agree_on_what_is_supported():
+    """Every refusal rule, one layout each (and the nearest accepted neighbour): the planner returns
+    UNSUPPORTED exactly where the oracle's check_supported raises."""
+    dense = oracle.ModelSpec(n_layers=6, hidden=64, n_q_heads=8, n_kv_heads=2, ffn=96, vocab=128, glu=True)
+    moe = oracle.ModelSpec(n_layers=4, hidden=32, n_q_heads=4, n_kv_heads=4, ffn=48, vocab=64, glu=True, n_experts=4)
+    L = oracle.Layout
+    cases = [
+        (dense, L(2, 1, 1), True), (dense, L(3, 1, 1), False),                      # ffn % tp, heads
+        (dense, L(4, 1, 1), True), (dense, L(8, 1, 1), True), (dense, L(16, 1, 1), False),   # kv heads split / replicated / too thin
+        (dense, L(1, 3, 1), True), (dense, L(1, 4, 1), False),                       # layers over stages
+        (dense, L(1, 3, 1, vpp=2), True), (dense, L(1, 2, 1, vpp=2), False),        # interleaved chunks
+        (dense, L(1, 3, 1, pp_first=2), True), (dense, L(1, 3, 1, pp_first=1), False),   # 6-1 = 5 over 2 stages
+        (dense, L(1, 3, 1, pp_first=2, pp_last=2), True), (dense, L(1, 2, 1, pp_first=2, pp_last=2), False),
+        (dense, L(1, 2, 1, pp_first=2, vpp=2), False),                               # uneven and interleaved
+        (dense, L(8, 1, 1, vocab_multiple=4), True),
+        (oracle.ModelSpec(n_layers=2, hidden=64, n_q_heads=8, n_kv_heads=8, ffn=96, vocab=100), L(8, 1, 1), False),   # vocab % tp
+        (oracle.ModelSpec(n_layers=2, hidden=64, n_q_heads=8, n_kv_heads=8, ffn=96, vocab=100), L(8, 1, 1, vocab_multiple=2), True),
+        (dense, L(1, 1, 2, ep=2), False),                                            # expert parallelism without experts
+        (moe, L(1, 1, 4, ep=2), True), (moe, L(1, 1, 3, ep=2), False),              # ep must divide dp
+        (moe, L(1, 1, 8, ep=8), False), (moe, L(1, 1, 4, ep=4), True),              # ep must divide the expert count
+    ]
+    for spec, lay, ok in cases:
+        try:
+            oracle.check_supported(spec, lay)
+            oracle_ok = True
+        except ValueError:
+            oracle_ok = False
+        s, a, b = lv_objects(spec, lay, lay)
+        try:
+            lv.liver_plan_create(s, a, b, 4096)
+            planner_ok = True
+        except lv.LiverError as e:
+            assert e.code == -2, (lay, e)
+            planner_ok = False
+        assert oracle_ok == planner_ok == ok, (spec, lay, oracle_ok, planner_ok, ok)
