@@ -454,3 +454,30 @@ def test_fused_cast_on_all_2_32_bit_patterns():
                 oracle_checked += b - a
     assert oracle_checked == 2 * 0x00810000
     print("all 2^32 patterns ok", flush=True)
+
+
+def test_data_calls_allocate_no_device_memory(gpt2):
+    """Bounded memory (Appendix A.1, Theorem 1): beyond the caller's buffers and one staging chunk the library holds
+    only the plan's descriptor table.  Free device memory, as the driver reports it, drops by about the table size
+    at plan creation and does not move across pack / unpack / reshard calls."""
+    cfg, spec, src, dst, world, want, dev = gpt2
+    out = alloc_dst(_plan(spec, src, dst, cfg["chunk_bytes"]))
+    staging = torch.empty(cfg["chunk_bytes"], dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    plan = _plan(spec, src, dst, cfg["chunk_bytes"])
+    info = lv.liver_plan_info(plan)
+    free1, _ = torch.cuda.mem_get_info()
+    assert 0 <= free0 - free1 <= max(4 << 20, 2 * info.table_bytes_device)       # allocation granularity: 2 MiB pages
+    for _ in range(3):
+        lv.liver_reshard(plan, dev, out)
+        for c in range(info.n_chunks):
+            lv.liver_pack(plan, c, dev, staging)
+            lv.liver_unpack(plan, c, staging, out)
+    torch.cuda.synchronize()
+    free2, _ = torch.cuda.mem_get_info()
+    assert free2 == free1
+    check_against(out, want, plan, "after repeated calls")
+    lv.liver_plan_destroy(plan)
+    free3, _ = torch.cuda.mem_get_info()
+    assert free3 == free0
