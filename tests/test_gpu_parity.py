@@ -461,9 +461,14 @@ def test_data_calls_allocate_no_device_memory(gpt2):
     only the plan's descriptor table.  Free device memory, as the driver reports it, drops by about the table size
     at plan creation and does not move across pack / unpack / reshard calls."""
     cfg, spec, src, dst, world, want, dev = gpt2
-    out = alloc_dst(_plan(spec, src, dst, cfg["chunk_bytes"]))
+    warm = _plan(spec, src, dst, cfg["chunk_bytes"])
+    out = alloc_dst(warm)
     staging = torch.empty(cfg["chunk_bytes"], dtype=torch.uint8, device="cuda")
+    lv.liver_reshard(warm, dev, out)          # the runtime loads the kernels' code objects on their first launch
+    lv.liver_pack(warm, 0, dev, staging)
+    lv.liver_unpack(warm, 0, staging, out)
     torch.cuda.synchronize()
+    lv.liver_plan_destroy(warm)
     free0, _ = torch.cuda.mem_get_info()
     plan = _plan(spec, src, dst, cfg["chunk_bytes"])
     info = lv.liver_plan_info(plan)
