@@ -263,3 +263,11 @@ def test_llama7b_round_trip_returns_every_bit():
     torch.cuda.synchronize()
     for key in B:
         assert torch.equal(B[key], B2[key]), key
+
+
+def test_llama13b_through_a_5_gib_staging_chunk():
+    """Wire offsets beyond 2^32: the 13B optimizer-state share streamed through two 5 GiB chunks (6.06 GiB of payload)."""
+    cfg = dict(synth.CONFIGS["llama13b_dp"], name="llama13b 5 GiB chunks", chunk_bytes=5 << 30)
+    ospec = oracle.ModelSpec(**cfg["spec"])
+    names = _layer(ospec, 26, ("o.w", "gate.w")) + _layer(ospec, 28, ("q.w", "down.w", "ln2.w")) + _layer(ospec, 30, ("k.w", "v.w", "o.w"))
+    _run(cfg, names)
