@@ -17,6 +17,16 @@ pytestmark = pytest.mark.gpu
 NP = {0: np.uint16, 1: np.uint32, 2: np.uint32, 3: np.uint32}
 
 
+@pytest.fixture(autouse=True)
+def _release_cached_blocks():
+    """These tests fill most of the HBM with differently sized buffers: hand the allocator's cached blocks back
+    between them, so that one test's leftovers cannot fragment the next one's 90 GB of allocations."""
+    yield
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
 def _setup(name):
     if isinstance(name, dict):
         cfg = name
