@@ -551,18 +551,22 @@ def reshard_state(spec: ModelSpec, src: Layout, dst: Layout,
 
 
 def expected_shards(spec: ModelSpec, lay: Layout, logical: Dict[str, np.ndarray],
-                    tps: Optional[Iterable[int]] = None, pps: Optional[Iterable[int]] = None):
+                    tps: Optional[Iterable[int]] = None, pps: Optional[Iterable[int]] = None, kind: int = PARAM):
     """For a subset of logical tensors: yield (tp, pp, stage_view, param, shard)
     for every physical parameter of world `lay` (optionally only rank columns
     tps x pps) built only from that subset.  Lets a caller verify a few tensors
-    of a very large state one at a time."""
+    of a very large state one at a time.  `kind` selects the buffer family: a
+    dense kind walks the dense buffers, an expert kind the expert buffers of
+    every expert-parallel index (the stage view names the DP ranks that share it)."""
     have = set(logical)
-    for pp in (range(lay.pp) if pps is None else pps):
-        for tp in (range(lay.tp) if tps is None else tps):
-            sv = stage_view(spec, lay, tp, pp)
-            for prm in sv.params:
-                if prm.blocks and all(b.name in have for b in prm.blocks):
-                    yield tp, pp, sv, prm, build_shard(prm, logical, logical[prm.blocks[0].name].dtype)
+    tps, pps = (None if tps is None else set(tps)), (None if pps is None else set(pps))
+    for tp, pp, ep in columns(lay, kind):
+        if (tps is not None and tp not in tps) or (pps is not None and pp not in pps):
+            continue
+        sv = stage_view(spec, lay, tp, pp, ep)
+        for prm in sv.params:
+            if prm.blocks and all(b.name in have for b in prm.blocks):
+                yield tp, pp, sv, prm, build_shard(prm, logical, logical[prm.blocks[0].name].dtype)
 
 
 __all__ = ["PARAM", "MASTER", "ADAM_M", "ADAM_V", "KINDS", "EXPERT_PARAM", "EXPERT_MASTER", "EXPERT_ADAM_M",

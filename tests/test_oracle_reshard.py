@@ -203,3 +203,30 @@ def test_copy_and_derive_agree_when_param_is_bf16_of_master(tiny_world):
     wa = make_world(spec, A, state)
     assert_same(oracle.reshard_state(spec, A, B, wa, derive_bf16=True),
                 oracle.reshard_state(spec, A, B, wa, derive_bf16=False), "derive vs copy")
+
+
+@pytest.mark.parametrize("lay", [oracle.Layout(2, 2, 4, 4, ep=2, bucket_elems=300), oracle.Layout(1, 1, 2, 1, ep=1), oracle.Layout(2, 1, 4, 8, ep=4)])
+def test_expected_shards_places_the_same_elements_as_the_full_split(lay):
+    """expected_shards (the tensor-at-a-time helper used at full size) against split_logical (the full split):
+    every shard it yields, written at its offset through dp_pieces, reproduces the full buffers; all kinds,
+    dense and expert."""
+    spec = MOE
+    state = tiny_state(spec, seed=3)
+    for kind in oracle.kinds_of(spec):
+        logical = {n: a for n, a in state[kind % 4].items() if (".x" in n) == (kind >= oracle.EXPERT_PARAM)}
+        full = oracle.split_logical(spec, lay, kind, logical)
+        got = {key: np.zeros_like(a) for key, a in full.items()}
+        some = {n: logical[n] for n in list(logical)[::2]}          # a subset yields only parameters it covers fully
+        for tp, pp, sv, prm, shard in oracle.expected_shards(spec, lay, some, kind=kind):
+            assert all(b.name in some for b in prm.blocks)
+        for tp, pp, sv, prm, shard in oracle.expected_shards(spec, lay, logical, kind=kind):
+            flat = shard.ravel()
+            if kind % 4 == 0:
+                for d in sv.dp_ranks:
+                    got[(lay.rank(tp, pp, d), kind)][prm.offset:prm.offset + prm.size] = flat
+            else:
+                for d, local, at, n in oracle.dp_pieces(sv, lay, prm.offset, prm.offset + prm.size):
+                    got[(lay.rank(tp, pp, d), kind)][local:local + n] = flat[at - prm.offset:at - prm.offset + n]
+        assert set(got) == set(full)
+        for key in full:
+            assert np.array_equal(got[key], full[key]), key
