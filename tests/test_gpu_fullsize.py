@@ -281,3 +281,112 @@ def test_llama13b_through_a_5_gib_staging_chunk():
     ospec = oracle.ModelSpec(**cfg["spec"])
     names = _layer(ospec, 26, ("o.w", "gate.w")) + _layer(ospec, 28, ("q.w", "down.w", "ln2.w")) + _layer(ospec, 30, ("k.w", "v.w", "o.w"))
     _run(cfg, names)
+
+
+# ---------------------------------------------------------------- mixture of experts at full size
+def _moe_world(ospec, olay, lay, plan, side, device):
+    """Source buffers of an MoE world generated in device memory: {(rank, kind): tensor}.  Dense buffers per
+    (tp, pp) column over all DP ranks, expert buffers per (tp, pp, ep) column over the DP ranks ep, ep+EP, ...;
+    only the first replica of each bf16 buffer exists (the only one a reshard reads)."""
+    bufs = {}
+    for fam, base in ((None, 0), ("x", 4)):
+        sizes, members = {}, {}
+        for tp, pp, ep in oracle.columns(olay, base):
+            sv = oracle.stage_view(ospec, olay, tp, pp, ep)
+            for j, d in enumerate(sv.dp_ranks):
+                n = lv.liver_plan_buffer_bytes(plan, side, lay.rank(tp, pp, d), base + 1) // 4
+                assert n == sv.S
+                sizes[((tp, pp, -1 if ep is None else ep), j)] = n
+            members[(tp, pp, -1 if ep is None else ep)] = sv.dp_ranks
+        group = len(next(iter(members.values())))
+        gen = synth.fill_device_world(sizes, group, synth.SEED_BASE + base, device=device)
+        for col, ranks in members.items():
+            for j, d in enumerate(ranks):
+                r = lay.rank(col[0], col[1], d)
+                for k in (1, 2, 3):
+                    bufs[(r, base + k)] = gen[(col, j, k)]
+            bufs[(lay.rank(col[0], col[1], ranks[0]), base)] = gen[(col, "param")]
+    return bufs
+
+
+_WORD = {k: (np.uint16 if k % 4 == 0 else np.uint32) for k in range(8)}
+_TT = {k: (torch.int16 if k % 4 == 0 else torch.int32) for k in range(8)}
+
+
+def _moe_expected(ospec, osrc, odst, src_bufs, names):
+    """Sampled logical tensors, every kind of both families, gathered from the source buffers and re-split by the
+    oracle: [(target rank, kind, offset in its buffer, expected words, parameter name)]."""
+    def read(rank, kind, lo, hi):
+        return src_bufs[(rank, kind)][lo:hi].view(_TT[kind]).cpu().numpy().view(_WORD[kind])
+    out = []
+    for k in oracle.kinds_of(ospec):
+        logical = oracle.gather_logical(ospec, osrc, k, read, names=names)
+        for tp, pp, sv, prm, shard in oracle.expected_shards(ospec, odst, logical, kind=k):
+            flat = shard.ravel()
+            pieces = [(d, prm.offset, prm.offset, prm.size) for d in sv.dp_ranks] if k % 4 == 0 \
+                else oracle.dp_pieces(sv, odst, prm.offset, prm.offset + prm.size)
+            out += [(odst.rank(tp, pp, d), k, local, flat[at - prm.offset:at - prm.offset + n], prm.name) for d, local, at, n in pieces]
+        print(f"  oracle: kind {k} gathered and split", flush=True)
+    return out
+
+
+def _moe_compare(expected, dst_bufs, what):
+    n_checked = 0
+    for rank, k, local, want, name in expected:
+        got = dst_bufs[(rank, k)][local:local + want.size].view(_TT[k]).cpu().numpy().view(_WORD[k])
+        assert np.array_equal(got, want), (what, name, "rank", rank, "kind", k)
+        n_checked += want.size
+    assert n_checked > 0
+    return n_checked
+
+
+def _moe_run(spec_kw, src_kw, dst_kw, chunk_bytes, names, device="cuda", runner=None):
+    ospec = oracle.ModelSpec(**spec_kw)
+    osrc, odst = oracle.Layout(**src_kw), oracle.Layout(**dst_kw)
+    spec, src, dst = lv.ModelSpec(**spec_kw), lv.Layout(**src_kw), lv.Layout(**dst_kw)
+    plan = lv.liver_plan_create(spec, src, dst, chunk_bytes)
+    info = lv.liver_plan_info(plan)
+    print(f"moe: generating state, {(info.bytes_read + info.bytes_written) / 1e9:.2f} GB to move, {info.n_desc} descriptors", flush=True)
+    src_bufs = _moe_world(ospec, osrc, src, plan, 0, device)
+    for (r, k) in src_bufs:
+        assert lv.liver_plan_buffer_used(plan, 0, r, k), (r, k)
+    dst_bufs = {}
+    for r in range(dst.n_ranks):
+        for k in range(8):
+            if lv.liver_plan_buffer_used(plan, 1, r, k):
+                n = lv.liver_plan_buffer_bytes(plan, 1, r, k) // (2 if k % 4 == 0 else 4)
+                dst_bufs[(r, k)] = torch.full((n,), -23131 if k % 4 == 0 else -1515870811,
+                                              dtype=torch.int16 if k % 4 == 0 else torch.int32, device=device)
+    print("moe: direct reshard", flush=True)
+    if runner is None:
+        lv.liver_reshard(plan, src_bufs, dst_bufs)
+        torch.cuda.synchronize()
+    else:
+        runner(plan, src_bufs, dst_bufs, False)
+    expected = _moe_expected(ospec, osrc, odst, src_bufs, names)
+    n = _moe_compare(expected, dst_bufs, "direct")
+    print(f"moe: direct ok on {n} sampled elements; staged path, {info.n_chunks} chunks", flush=True)
+    for t in dst_bufs.values():
+        t.fill_(-7)
+    if runner is None:
+        staging = torch.empty(chunk_bytes, dtype=torch.uint8, device=device)
+        for c in range(info.n_chunks):
+            lv.liver_pack(plan, c, src_bufs, staging)
+            lv.liver_unpack(plan, c, staging, dst_bufs)
+        torch.cuda.synchronize()
+    else:
+        runner(plan, src_bufs, dst_bufs, True)
+    _moe_compare(expected, dst_bufs, "staged")
+    print("moe: staged ok", flush=True)
+
+
+def test_mixture_of_experts_at_full_size():
+    """A 6.7 B-parameter MoE (8 layers, 8 experts of FFN 7168, GQA 32/8): TP2.PP2.DP4.EP4 -> TP4.PP1.DP4.EP2, all
+    eight buffer kinds, about 100 GB per world; sampled dense and expert tensors against the oracle."""
+    spec_kw = dict(n_layers=8, hidden=4096, n_q_heads=32, n_kv_heads=8, ffn=7168, vocab=32000, max_pos=0, glu=True,
+                   norm_bias=False, linear_bias=False, tied_embed=False, n_experts=8)
+    names = ["embed.word", "lm_head.w", "final_norm.w", "L0.router.w", "L0.q.w", "L0.k.w", "L0.v.w", "L0.o.w", "L0.ln1.w",
+             "L0.x0.gate.w", "L0.x0.up.w", "L0.x0.down.w", "L3.x5.gate.w", "L3.x5.up.w", "L3.x5.down.w", "L4.x2.down.w",
+             "L7.x7.gate.w", "L7.x7.up.w", "L7.x7.down.w", "L7.router.w", "L7.ln2.w"]
+    _moe_run(spec_kw, dict(tp=2, pp=2, dp=4, pad_multiple=128, ep=4), dict(tp=4, pp=1, dp=4, pad_multiple=128, ep=2),
+             256 << 20, names)
