@@ -459,7 +459,8 @@ def test_fused_cast_on_all_2_32_bit_patterns():
 def test_data_calls_allocate_no_device_memory(gpt2):
     """Bounded memory (Appendix A.1, Theorem 1): beyond the caller's buffers and one staging chunk the library holds
     only the plan's descriptor table.  Free device memory, as the driver reports it, drops by about the table size
-    at plan creation and does not move across pack / unpack / reshard calls."""
+    at plan creation and stays there across pack / unpack / reshard calls of 4 GB each (up to a few MiB of the
+    runtime's own pools)."""
     cfg, spec, src, dst, world, want, dev = gpt2
     warm = _plan(spec, src, dst, cfg["chunk_bytes"])
     out = alloc_dst(warm)
@@ -470,6 +471,7 @@ def test_data_calls_allocate_no_device_memory(gpt2):
     torch.cuda.synchronize()
     lv.liver_plan_destroy(warm)
     free0, _ = torch.cuda.mem_get_info()
+    slack = 8 << 20          # the HIP runtime grows its own small pools (kernel arguments, signals) in 2 MiB pages
     plan = _plan(spec, src, dst, cfg["chunk_bytes"])
     info = lv.liver_plan_info(plan)
     free1, _ = torch.cuda.mem_get_info()
@@ -481,8 +483,8 @@ def test_data_calls_allocate_no_device_memory(gpt2):
             lv.liver_unpack(plan, c, staging, out)
     torch.cuda.synchronize()
     free2, _ = torch.cuda.mem_get_info()
-    assert free2 == free1
+    assert abs(free2 - free1) <= slack, (free1, free2)
     check_against(out, want, plan, "after repeated calls")
     lv.liver_plan_destroy(plan)
     free3, _ = torch.cuda.mem_get_info()
-    assert free3 == free0
+    assert abs(free3 - free0) <= slack, (free0, free3)
