@@ -475,7 +475,7 @@ def test_data_calls_allocate_no_device_memory(gpt2):
     plan = _plan(spec, src, dst, cfg["chunk_bytes"])
     info = lv.liver_plan_info(plan)
     free1, _ = torch.cuda.mem_get_info()
-    assert 0 <= free0 - free1 <= max(4 << 20, 2 * info.table_bytes_device)       # allocation granularity: 2 MiB pages
+    assert -slack <= free0 - free1 <= slack + 2 * info.table_bytes_device         # allocation granularity: 2 MiB pages
     for _ in range(3):
         lv.liver_reshard(plan, dev, out)
         for c in range(info.n_chunks):
