@@ -206,9 +206,16 @@ int liver_plan_create(const liver_model_spec_t* spec, const liver_layout_t* src,
  * synchronised every stream that still runs a kernel of this plan. */
 void liver_plan_destroy(liver_plan_t* plan);
 
+/* What the plan costs and moves: descriptor counts, wire bytes, bytes read and written, and
+ * table_bytes_device, the plan's only device allocation -- the "transfer-plan metadata" term C of the
+ * bounded-memory guarantee (Appendix A.1, Table 3 and Theorem 1: extra memory <= B + C).  `out` is a
+ * caller-owned struct; nothing else is touched.  INVALID_ARG on a null pointer. */
 int liver_plan_info(const liver_plan_t* plan, liver_plan_info_t* out);
 
-/* Size in bytes of buffer (side: 0 = source world, 1 = target world; rank; kind). */
+/* Size in bytes of buffer (side: 0 = source world, 1 = target world; rank; kind): the extent of what the
+ * sharding function S(T, r, C) of Appendix A.2.1 assigns to rank r under that world's configuration, laid out
+ * as this header describes (N_pad bf16 elements for PARAM kinds, N_pad/DP fp32 elements for the others; 0 for
+ * the expert kinds of a dense model).  INVALID_ARG on a null pointer or an index out of range. */
 int liver_plan_buffer_bytes(const liver_plan_t* plan, int side, int rank, int kind, size_t* out);
 
 /* 1 if any descriptor reads (side 0) / writes (side 1) that buffer, 0 if not,
@@ -219,7 +226,10 @@ int liver_plan_buffer_used(const liver_plan_t* plan, int side, int rank, int kin
 int64_t liver_plan_desc_count(const liver_plan_t* plan, int list);
 int liver_plan_desc(const liver_plan_t* plan, int list, int64_t i, liver_desc_t* out);
 
-/* Launch shape of the copy kernels: grid_blocks workgroups of 256 threads
+/* Launch shape of the copy kernels (a tuning knob of this implementation; the paper has no counterpart).
+ * A plan is immutable and may be used from several threads and streams at once, with ONE exception: this
+ * call, which is meant for the time between liver_plan_create and the plan's first data call.
+ * grid_blocks workgroups of 256 threads
  * (0 = default: one per compute unit); tile_order 0 = each workgroup walks one
  * contiguous range of tiles, 1 = workgroups interleave tile by tile, 2 = groups
  * of up to 64 tiles visited in a scattered (multiplicative-permutation) order,
@@ -249,43 +259,22 @@ int liver_unpack(const liver_plan_t* plan, int chunk, const void* staging, void*
 int liver_reshard(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs,
                   void* hip_stream);
 
-/* The whole staged reshard as a pipeline (the single-GPU analogue of Section 5:
- * "the transfer is pipelined using isend() and irecv()"): chunk k is packed into
+/* The whole staged reshard as a pipeline (the single-GPU analogue of the pipelined
+ * point-to-point transfer through fixed-size chunks of Section 5): chunk k is packed into
  * staging[k % n_staging] on stream_pack while earlier chunks are unpacked on
  * stream_unpack; events order pack(k) -> unpack(k) -> pack(k + n_staging).  Extra
  * device memory is still O(B): n_staging chunks of chunk_bytes (1 <= n_staging <=
  * 8; `staging` is a host array of device pointers).  The two streams may be the
  * same.  Returns after enqueueing; all work has completed once stream_unpack has
  * been synchronised.  Creates and destroys 2*n_staging HIP events per call (host
- * objects; no device memory is allocated). */
+ * objects; no device memory is allocated).  Every chunk's buffers are validated before the
+ * first kernel is enqueued, so an argument error writes nothing. */
 int liver_reshard_staged(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs,
                          void* const* staging, int n_staging, void* stream_pack, void* stream_unpack);
 
+/* Plumbing (no counterpart in the paper): text for a LIVER_E_* code, followed by the detail of the calling
+ * thread's last failure if that failure had this code.  The pointer is valid until the thread's next call. */
 const char* liver_strerror(int code);
-
-/* Debugging aid, never called by the entry points above (there is no CPU
- * fallback): executes the plan's LOWERED descriptor tables -- what the kernels
- * would run for list `list` (LIVER_LIST_*; `chunk` is ignored for the direct
- * list) -- on HOST memory, unit by unit, and returns LIVER_E_HIP instead of
- * performing any access that is out of bounds or misaligned.  Buffers are host
- * arrays with the sizes liver_plan_buffer_bytes reports; staging has chunk_bytes. */
-int liver_debug_emulate_host(const liver_plan_t* plan, int list, int chunk, const void* const* src_bufs,
-                             void* const* dst_bufs, void* staging);
-
-/* Measurement aid, never called by the entry points above: enqueues on `hip_stream`
- * the plainest streaming kernel of the library's launch shape (256-thread
- * workgroups, grid-stride over 32 KiB tiles, 16-byte non-temporal accesses) over
- * `bytes` bytes of DEVICE memory, so that a benchmark can quote what a plain
- * read, fill or copy reaches on the same buffers the reshard uses.
- *   mode 0  read src[0, bytes); additionally stores 16 bytes per workgroup into
- *           dst[0, grid*16) (dst must hold at least that; grid*16 <= bytes)
- *   mode 1  fill dst[0, bytes) with a fixed pattern (src is ignored)
- *   mode 2  copy src[0, bytes) to dst[0, bytes)
- * bytes: positive multiple of 32768; grid: 1..65536 workgroups; pointers 16-byte
- * aligned, owned by the caller, not overlapping.  Asynchronous, allocates
- * nothing.  LIVER_E_INVALID_ARG on a bad argument (nothing is launched),
- * LIVER_E_HIP if the launch fails. */
-int liver_debug_bandwidth_probe(int mode, const void* src, void* dst, size_t bytes, int grid, void* hip_stream);
 
 #ifdef __cplusplus
 }

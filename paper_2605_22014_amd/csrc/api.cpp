@@ -6,35 +6,47 @@
 #include <string>
 
 #include "launch.hpp"
+#include "liver_debug.h"
 #include "plan.hpp"
 
 namespace {
 
 thread_local std::string g_last_detail;
+thread_local int g_last_code = LIVER_OK;
 
 int fail(int code, const std::string& detail) {
     g_last_detail = detail;
+    g_last_code = code;
     return code;
 }
 
 int n_ranks(const liver_layout_t& l) { return l.tp * l.pp * l.dp; }
 
-// Resolve the buffers of passes [p0, p1) of `list` and launch them in order.
-// Everything is validated before the first launch, so an error writes nothing.
-int run_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uint32_t p1, const void* const* src_bufs,
-               void* const* dst_bufs, const void* staging, void* hip_stream, int default_hints) {
+const void* resolve(const liver::BufRef& r, const void* const* src_bufs, void* const* dst_bufs, const void* staging) {
+    return r.side == 0   ? (src_bufs ? src_bufs[(size_t)r.rank * LIVER_NUM_KINDS + r.kind] : nullptr)
+           : r.side == 1 ? (dst_bufs ? dst_bufs[(size_t)r.rank * LIVER_NUM_KINDS + r.kind] : nullptr)
+                         : staging;
+}
+
+// Everything that can be refused about passes [p0, p1) of `list`, checked without enqueuing anything.
+int check_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uint32_t p1, const void* const* src_bufs,
+                 void* const* dst_bufs, const void* staging) {
     if (plan->device < 0) return fail(LIVER_E_NO_DEVICE, "plan was created without a HIP device");
     int cur = -1;
     if (hipGetDevice(&cur) != hipSuccess || cur != plan->device)
         return fail(LIVER_E_INVALID_ARG, "current HIP device is not the one the plan was created on");
     for (uint32_t p = p0; p < p1; ++p)
         for (const liver::BufRef& r : list.passes[p].bufs) {
-            const void* ptr = r.side == 0   ? (src_bufs ? src_bufs[(size_t)r.rank * LIVER_NUM_KINDS + r.kind] : nullptr)
-                              : r.side == 1 ? (dst_bufs ? dst_bufs[(size_t)r.rank * LIVER_NUM_KINDS + r.kind] : nullptr)
-                                            : staging;
+            const void* ptr = resolve(r, src_bufs, dst_bufs, staging);
             if (!ptr) return fail(LIVER_E_INVALID_ARG, "a buffer the plan uses is NULL");
             if ((uintptr_t)ptr % 16) return fail(LIVER_E_INVALID_ARG, "buffers must be 16-byte aligned");
         }
+    return LIVER_OK;
+}
+
+// Enqueue passes [p0, p1) of `list` in order; check_passes has accepted them.
+int launch_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uint32_t p1, const void* const* src_bufs,
+                  void* const* dst_bufs, const void* staging, void* hip_stream, int default_hints) {
     // Default launch shape: one persistent 256-thread workgroup per compute unit.  Measured on MI355X
     // at the 7B shape, 1-2 workgroups per CU reach the same plateau and more only add DRAM page conflicts.
     const uint32_t max_grid = plan->grid_blocks > 0 ? (uint32_t)plan->grid_blocks : (uint32_t)plan->n_cu;
@@ -55,8 +67,7 @@ int run_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uin
         // scattered order: groups of up to 64 tiles (4 MiB), at least ~32 groups per workgroup; the groups
         // are visited in a multiplicative permutation with a multiplier near 0.618 * n_groups
         {
-            const uint32_t g_max = plan->grid_blocks > 0 ? (uint32_t)plan->grid_blocks : (uint32_t)plan->n_cu;
-            uint32_t group = pass.n_tiles / (g_max * 32u);
+            uint32_t group = pass.n_tiles / (max_grid * 32u);
             group = group < 1 ? 1 : group > 64 ? 64 : group;
             const uint32_t n_groups = (pass.n_tiles + group - 1) / group;
             uint32_t mul = (uint32_t)(0.6180339887 * n_groups) | 1u;
@@ -66,11 +77,7 @@ int run_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uin
             args.group = group, args.perm_mul = mul;
         }
         size_t i = 0;
-        for (const liver::BufRef& r : pass.bufs) {
-            const void* ptr = r.side == 0 ? src_bufs[(size_t)r.rank * LIVER_NUM_KINDS + r.kind]
-                              : r.side == 1 ? dst_bufs[(size_t)r.rank * LIVER_NUM_KINDS + r.kind] : staging;
-            args.bufs[i++] = (char*)ptr;
-        }
+        for (const liver::BufRef& r : pass.bufs) args.bufs[i++] = (char*)resolve(r, src_bufs, dst_bufs, staging);
         for (; i < (size_t)liver::MAX_PASS_BUFS; ++i) args.bufs[i] = nullptr;
         const uint32_t grid = pass.n_tiles < max_grid ? pass.n_tiles : max_grid;
         hipError_t e = liver::launch_pass(args, grid, hints, (hipStream_t)hip_stream);
@@ -78,6 +85,18 @@ int run_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uin
     }
     return LIVER_OK;
 }
+
+// Validate, then launch: an argument error writes nothing.
+int run_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, uint32_t p1, const void* const* src_bufs,
+               void* const* dst_bufs, const void* staging, void* hip_stream, int default_hints) {
+    const int rc = check_passes(plan, list, p0, p1, src_bufs, dst_bufs, staging);
+    if (rc != LIVER_OK) return rc;
+    return launch_passes(plan, list, p0, p1, src_bufs, dst_bufs, staging, hip_stream, default_hints);
+}
+
+constexpr int HINT_PACK = 1;    // the source is streamed once, the staging chunk is re-read by unpack
+constexpr int HINT_UNPACK = 2;  // the staging chunk was just written, the targets are streamed
+constexpr int HINT_DIRECT = 3;  // every byte is touched once
 
 }  // namespace
 
@@ -190,7 +209,7 @@ int liver_pack(const liver_plan_t* plan, int chunk, const void* const* src_bufs,
     if (chunk < 0 || chunk >= plan->info.n_chunks) return fail(LIVER_E_INVALID_ARG, "chunk index out of range");
     if ((uintptr_t)staging % 256) return fail(LIVER_E_INVALID_ARG, "staging must be 256-byte aligned");
     return run_passes(plan, plan->pack, plan->pack.chunk_pass[chunk], plan->pack.chunk_pass[chunk + 1], src_bufs, nullptr,
-                      staging, hip_stream, /*source is streamed once, staging is re-read by unpack*/ 1);
+                      staging, hip_stream, HINT_PACK);
 }
 
 int liver_unpack(const liver_plan_t* plan, int chunk, const void* staging, void* const* dst_bufs, void* hip_stream) {
@@ -198,13 +217,13 @@ int liver_unpack(const liver_plan_t* plan, int chunk, const void* staging, void*
     if (chunk < 0 || chunk >= plan->info.n_chunks) return fail(LIVER_E_INVALID_ARG, "chunk index out of range");
     if ((uintptr_t)staging % 256) return fail(LIVER_E_INVALID_ARG, "staging must be 256-byte aligned");
     return run_passes(plan, plan->unpack, plan->unpack.chunk_pass[chunk], plan->unpack.chunk_pass[chunk + 1], nullptr,
-                      dst_bufs, staging, hip_stream, /*staging was just written, targets are streamed*/ 2);
+                      dst_bufs, staging, hip_stream, HINT_UNPACK);
 }
 
 int liver_reshard(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs, void* hip_stream) {
     if (!plan || !src_bufs || !dst_bufs) return fail(LIVER_E_INVALID_ARG, "null argument");
     return run_passes(plan, plan->direct, 0, (uint32_t)plan->direct.passes.size(), src_bufs, dst_bufs, nullptr, hip_stream,
-                      /*every byte is touched once*/ 3);
+                      HINT_DIRECT);
 }
 
 int liver_reshard_staged(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs,
@@ -216,7 +235,11 @@ int liver_reshard_staged(const liver_plan_t* plan, const void* const* src_bufs, 
         for (int j = 0; j < i; ++j)
             if (staging[i] == staging[j]) return fail(LIVER_E_INVALID_ARG, "staging chunks must be distinct");
     }
-    if (plan->device < 0) return fail(LIVER_E_NO_DEVICE, "plan was created without a HIP device");
+    // every chunk's buffers are checked before the first kernel is enqueued: an argument error writes nothing
+    int rc = check_passes(plan, plan->pack, 0, (uint32_t)plan->pack.passes.size(), src_bufs, nullptr, staging[0]);
+    if (rc == LIVER_OK)
+        rc = check_passes(plan, plan->unpack, 0, (uint32_t)plan->unpack.passes.size(), nullptr, dst_bufs, staging[0]);
+    if (rc != LIVER_OK) return rc;
     const int n_chunks = (int)plan->info.n_chunks;
     hipStream_t sp = (hipStream_t)stream_pack, su = (hipStream_t)stream_unpack;
     hipEvent_t packed[8] = {}, unpacked[8] = {};
@@ -226,15 +249,18 @@ int liver_reshard_staged(const liver_plan_t* plan, const void* const* src_bufs, 
         e = hipEventCreateWithFlags(&packed[made], hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&unpacked[made], hipEventDisableTiming);
     }
-    int rc = LIVER_OK;
     for (int k = 0; k < n_chunks && e == hipSuccess && rc == LIVER_OK; ++k) {
         const int slot = k % n_staging;
         if (k >= n_staging) e = hipStreamWaitEvent(sp, unpacked[slot], 0);  // the chunk buffer is free again
-        if (e == hipSuccess) rc = liver_pack(plan, k, src_bufs, staging[slot], stream_pack);
+        if (e == hipSuccess)
+            rc = launch_passes(plan, plan->pack, plan->pack.chunk_pass[k], plan->pack.chunk_pass[k + 1], src_bufs, nullptr,
+                               staging[slot], stream_pack, HINT_PACK);
         if (rc != LIVER_OK) break;
         if (e == hipSuccess) e = hipEventRecord(packed[slot], sp);
         if (e == hipSuccess) e = hipStreamWaitEvent(su, packed[slot], 0);
-        if (e == hipSuccess) rc = liver_unpack(plan, k, staging[slot], dst_bufs, stream_unpack);
+        if (e == hipSuccess)
+            rc = launch_passes(plan, plan->unpack, plan->unpack.chunk_pass[k], plan->unpack.chunk_pass[k + 1], nullptr,
+                               dst_bufs, staging[slot], stream_unpack, HINT_UNPACK);
         if (rc != LIVER_OK) break;
         if (e == hipSuccess) e = hipEventRecord(unpacked[slot], su);
     }
@@ -242,7 +268,7 @@ int liver_reshard_staged(const liver_plan_t* plan, const void* const* src_bufs, 
         if (packed[i]) (void)hipEventDestroy(packed[i]);
         if (unpacked[i]) (void)hipEventDestroy(unpacked[i]);
     }
-    if (rc != LIVER_OK) return rc;
+    if (rc != LIVER_OK) return rc;  // a launch the runtime refused (LIVER_E_HIP): earlier chunks may have run
     if (e != hipSuccess) return fail(LIVER_E_HIP, std::string("staged pipeline: ") + hipGetErrorString(e));
     return LIVER_OK;
 }
@@ -273,7 +299,7 @@ const char* liver_strerror(int code) {
         case LIVER_E_NO_DEVICE: base = "no HIP device"; break;
     }
     msg = base;
-    if (!g_last_detail.empty()) msg += ": " + g_last_detail;
+    if (code == g_last_code && !g_last_detail.empty()) msg += ": " + g_last_detail;  // the detail of this thread's last failure
     return msg.c_str();
 }
 

@@ -7,6 +7,7 @@
 // liver_reshard) never call it: there is no CPU fallback.
 #include <cstring>
 
+#include "liver_debug.h"
 #include "plan.hpp"
 
 namespace {

@@ -234,28 +234,29 @@ __global__ __launch_bounds__(BLOCK) void liver_probe_kernel(const u32x4* __restr
     if (MODE == 0 && threadIdx.x == 0) b[blockIdx.x] = acc;  // lane 0's value: enough to keep every lane's loads
 }
 
+// Both launchers report the status of THEIR launch (hipLaunchKernel's own return value): an error that
+// some earlier call of the thread left behind is neither returned nor cleared here.
 hipError_t launch_probe(int mode, const void* src, void* dst, uint64_t n_tiles, uint32_t grid, hipStream_t stream) {
-    dim3 g(grid), b(BLOCK);
     const u32x4* a = (const u32x4*)src;
     u32x4* o = (u32x4*)dst;
-    switch (mode) {
-        case 0: hipLaunchKernelGGL((liver_probe_kernel<0>), g, b, 0, stream, a, o, n_tiles); break;
-        case 1: hipLaunchKernelGGL((liver_probe_kernel<1>), g, b, 0, stream, a, o, n_tiles); break;
-        default: hipLaunchKernelGGL((liver_probe_kernel<2>), g, b, 0, stream, a, o, n_tiles); break;
-    }
-    return hipGetLastError();
+    void* kargs[] = {(void*)&a, (void*)&o, (void*)&n_tiles};
+    const void* fn = mode == 0   ? (const void*)&liver_probe_kernel<0>
+                     : mode == 1 ? (const void*)&liver_probe_kernel<1>
+                                 : (const void*)&liver_probe_kernel<2>;
+    return hipLaunchKernel(fn, dim3(grid), dim3(BLOCK), kargs, 0, stream);
 }
 
 hipError_t launch_pass(const PassArgs& args, uint32_t grid, int cache_hints, hipStream_t stream) {
     if (args.n_tiles == 0 || args.n_desc == 0) return hipSuccess;
-    dim3 g(grid), b(BLOCK);
+    void* kargs[] = {(void*)&args};
+    const void* fn;
     switch (cache_hints & 3) {
-        case 0: hipLaunchKernelGGL((liver_copy_kernel<false, false>), g, b, 0, stream, args); break;
-        case 1: hipLaunchKernelGGL((liver_copy_kernel<true, false>), g, b, 0, stream, args); break;
-        case 2: hipLaunchKernelGGL((liver_copy_kernel<false, true>), g, b, 0, stream, args); break;
-        default: hipLaunchKernelGGL((liver_copy_kernel<true, true>), g, b, 0, stream, args); break;
+        case 0: fn = (const void*)&liver_copy_kernel<false, false>; break;
+        case 1: fn = (const void*)&liver_copy_kernel<true, false>; break;
+        case 2: fn = (const void*)&liver_copy_kernel<false, true>; break;
+        default: fn = (const void*)&liver_copy_kernel<true, true>; break;
     }
-    return hipGetLastError();
+    return hipLaunchKernel(fn, dim3(grid), dim3(BLOCK), kargs, 0, stream);
 }
 
 }  // namespace liver
