@@ -1,6 +1,10 @@
 """Randomised parity on the GPU: random models whose dimensions are multiples of 8 (so that the 16-byte
 vector paths, the fused copy + cast and the zero fills are exercised under random geometry) and random
-world pairs mixing every layout feature; direct and staged, copy and derive, bit for bit against the oracle."""
+world pairs mixing every layout feature; direct and staged, copy and derive, bit for bit against the oracle.
+
+A random plan never reaches the device unchecked: the library's bounds-checked host emulator first runs the
+very tables the kernels would run (direct list, every pack and unpack chunk) on host copies of the buffers; an
+offset outside a buffer, or a result that differs from the oracle's, fails the case before any kernel launch."""
 import numpy as np
 import pytest
 import torch
@@ -8,7 +12,7 @@ from hypothesis import HealthCheck, given, seed, settings, strategies as st
 
 import oracle
 import paper_2605_22014_amd as lv
-from interp import lv_objects
+from interp import lv_objects, emulate_direct, emulate_staged, used_dst
 from util import make_world, tiny_state, corrupt_replicas
 from gpu_util import to_dev, run_direct, run_staged, check_against
 from test_planner_fuzz import layouts
@@ -41,6 +45,14 @@ def cases(draw):
     return spec, src, dst, draw(st.booleans()), kw, draw(st.sampled_from([1024, 4096, 1 << 16])), draw(st.integers(0, 10 ** 6))
 
 
+def proven_on_host(plan, world, want):
+    """The plan's lowered tables stay inside the buffers and give the oracle's bits, shown on host memory by the
+    bounds-checked emulator (LiverError with LIVER_E_HIP on any access out of bounds)."""
+    for what, got in (("direct", emulate_direct(plan, world)), ("staged", emulate_staged(plan, world))):
+        for key in used_dst(plan):
+            assert np.array_equal(got[key].view(want[key].dtype), want[key]), ("host emulation", what, key)
+
+
 @seed(22014)
 @settings(max_examples=40, deadline=None, suppress_health_check=list(HealthCheck), derandomize=True, database=None)
 @given(cases())
@@ -53,6 +65,7 @@ def test_random_worlds_on_device(case):
     want = oracle.reshard_state(spec, src, dst, world, derive_bf16=derive)
     s, a, b = lv_objects(spec, src, dst, derive_bf16=derive, **kw)
     plan = lv.liver_plan_create(s, a, b, chunk)
+    proven_on_host(plan, world, want)             # raises before anything is launched
     dev = to_dev(world)
     check_against(run_direct(plan, dev), want, plan, "direct")
     check_against(run_staged(plan, dev), want, plan, "staged")
