@@ -272,6 +272,23 @@ int liver_reshard(const liver_plan_t* plan, const void* const* src_bufs, void* c
 int liver_reshard_staged(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs,
                          void* const* staging, int n_staging, void* stream_pack, void* stream_unpack);
 
+/* For callers that cannot allocate device memory at all -- code under HIP-graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: the whole staged reshard (pack and unpack of every chunk, in order,
+ * on `hip_stream`) through a staging chunk that the LIBRARY holds, a fixed device array of
+ * liver_static_staging_bytes() = 64 MiB that exists on every GPU from the moment the library is loaded until
+ * the process ends.  The caller passes source and target tables only.  The call allocates nothing (no
+ * hipMalloc / hipFree, no events), does not synchronise, and gives the same target bytes as liver_reshard and
+ * as liver_pack + liver_unpack with a caller's chunk.
+ * The plan must have been created with chunk_bytes <= liver_static_staging_bytes(); a larger one is refused
+ * with LIVER_E_INVALID_ARG before anything is enqueued (the message names both sizes).  Other errors as for
+ * liver_pack / liver_unpack; all buffers of all chunks are validated before the first launch.
+ * All calls on one GPU share that GPU's array: calls that may overlap in time there (different streams or
+ * threads) race on it -- serialise them.  The array keeps the previous call's bytes; nothing depends on
+ * them, since every byte of a chunk that is read was written by the same chunk's pack. */
+int liver_reshard_static(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs,
+                         void* hip_stream);
+size_t liver_static_staging_bytes(void);
+
 /* Plumbing (no counterpart in the paper): text for a LIVER_E_* code, followed by the detail of the calling
  * thread's last failure if that failure had this code.  The pointer is valid until the thread's next call. */
 const char* liver_strerror(int code);

@@ -135,6 +135,9 @@ def _load() -> C.CDLL:
     lib.liver_unpack.argtypes = [P, C.c_int, P, C.POINTER(P), P]
     lib.liver_reshard.argtypes = [P, C.POINTER(P), C.POINTER(P), P]
     lib.liver_reshard_staged.argtypes = [P, C.POINTER(P), C.POINTER(P), C.POINTER(P), C.c_int, P, P]
+    lib.liver_reshard_static.argtypes = [P, C.POINTER(P), C.POINTER(P), P]
+    lib.liver_static_staging_bytes.argtypes = []
+    lib.liver_static_staging_bytes.restype = C.c_size_t
     lib.liver_debug_emulate_host.argtypes = [P, C.c_int, C.c_int, C.POINTER(P), C.POINTER(P), P]
     lib.liver_debug_bandwidth_probe.argtypes = [C.c_int, P, P, C.c_size_t, C.c_int, P]
     lib.liver_strerror.argtypes = [C.c_int]
@@ -284,6 +287,15 @@ def liver_reshard_staged(plan: Plan, src_bufs, dst_bufs, staging, stream_pack=No
     _check(_lib.liver_reshard_staged(plan.handle, _table(src_bufs, plan.src.n_ranks, plan, 0),
                                      _table(dst_bufs, plan.dst.n_ranks, plan, 1),
                                      arr, len(staging), _stream(stream_pack), _stream(stream_unpack)))
+
+
+def liver_reshard_static(plan: Plan, src_bufs, dst_bufs, stream=None) -> None:
+    _check(_lib.liver_reshard_static(plan.handle, _table(src_bufs, plan.src.n_ranks, plan, 0),
+                                     _table(dst_bufs, plan.dst.n_ranks, plan, 1), _stream(stream)))
+
+
+def liver_static_staging_bytes() -> int:
+    return int(_lib.liver_static_staging_bytes())
 
 
 def liver_debug_emulate_host(plan: Plan, which: int, chunk: int, src_bufs, dst_bufs, staging) -> None:

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libliver.so")
-SOURCES = ["planner.cpp", "api.cpp", "emulate.cpp", "kernels.hip"]
+SOURCES = ["planner.cpp", "api.cpp", "emulate.cpp", "kernels.hip", "static_staging.hip"]
 
 
 def build(verbose: bool = False) -> str:

@@ -138,6 +138,8 @@ int liver_plan_create(const liver_model_spec_t* spec, const liver_layout_t* src,
             return fail(code, std::string("descriptor table upload: ") + hipGetErrorString(e));
         }
         plan->dev_table = table, plan->device = dev, plan->n_cu = cu > 0 ? cu : 256;
+        void* unused = nullptr;  // set-up is where the static staging array's address on this device is looked up;
+        (void)liver::static_staging(dev, &unused);  // a failure is reported by liver_reshard_static, which needs it
     } else {
         (void)hipGetLastError();  // no device: host-only plan
     }
@@ -271,6 +273,33 @@ int liver_reshard_staged(const liver_plan_t* plan, const void* const* src_bufs, 
     if (rc != LIVER_OK) return rc;  // a launch the runtime refused (LIVER_E_HIP): earlier chunks may have run
     if (e != hipSuccess) return fail(LIVER_E_HIP, std::string("staged pipeline: ") + hipGetErrorString(e));
     return LIVER_OK;
+}
+
+size_t liver_static_staging_bytes(void) { return liver::STATIC_STAGING_BYTES; }
+
+int liver_reshard_static(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs, void* hip_stream) {
+    if (!plan || !src_bufs || !dst_bufs) return fail(LIVER_E_INVALID_ARG, "null argument");
+    if (plan->chunk_bytes > liver::STATIC_STAGING_BYTES)
+        return fail(LIVER_E_INVALID_ARG, "the plan's chunk_bytes (" + std::to_string(plan->chunk_bytes) +
+                                             ") exceeds the library's static staging array (" +
+                                             std::to_string(liver::STATIC_STAGING_BYTES) +
+                                             " bytes): create the plan with a smaller chunk_bytes");
+    if (plan->device < 0) return fail(LIVER_E_NO_DEVICE, "plan was created without a HIP device");
+    void* staging = nullptr;
+    const hipError_t e = liver::static_staging(plan->device, &staging);  // resolved at plan creation; a lookup here
+    if (e != hipSuccess) return fail(LIVER_E_HIP, std::string("static staging array: ") + hipGetErrorString(e));
+    int rc = check_passes(plan, plan->pack, 0, (uint32_t)plan->pack.passes.size(), src_bufs, nullptr, staging);
+    if (rc == LIVER_OK)
+        rc = check_passes(plan, plan->unpack, 0, (uint32_t)plan->unpack.passes.size(), nullptr, dst_bufs, staging);
+    const int n_chunks = (int)plan->info.n_chunks;
+    for (int k = 0; k < n_chunks && rc == LIVER_OK; ++k) {  // one stream: pack(k), unpack(k), pack(k+1) run in order
+        rc = launch_passes(plan, plan->pack, plan->pack.chunk_pass[k], plan->pack.chunk_pass[k + 1], src_bufs, nullptr,
+                           staging, hip_stream, HINT_PACK);
+        if (rc == LIVER_OK)
+            rc = launch_passes(plan, plan->unpack, plan->unpack.chunk_pass[k], plan->unpack.chunk_pass[k + 1], nullptr,
+                               dst_bufs, staging, hip_stream, HINT_UNPACK);
+    }
+    return rc;
 }
 
 int liver_debug_bandwidth_probe(int mode, const void* src, void* dst, size_t bytes, int grid, void* hip_stream) {

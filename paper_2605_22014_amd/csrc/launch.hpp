@@ -27,4 +27,10 @@ hipError_t launch_pass(const PassArgs& args, uint32_t grid, int cache_hints, hip
 constexpr uint32_t PROBE_TILE_UNITS = 2048;  // 32 KiB per workgroup step
 hipError_t launch_probe(int mode, const void* src, void* dst, uint64_t n_tiles, uint32_t grid, hipStream_t stream);
 
+// The staging chunk the library itself holds on every device (a file-scope device array of
+// STATIC_STAGING_BYTES): *ptr = its address on `device`, which must be the current device the first
+// time it is asked for.  Never allocates.
+constexpr size_t STATIC_STAGING_BYTES = 64u << 20;
+hipError_t static_staging(int device, void** ptr);
+
 }  // namespace liver

@@ -52,3 +52,24 @@ def test_strerror_appends_the_detail_only_to_the_code_that_failed():
     assert lv.liver_strerror(-2).startswith("unsupported configuration: ")
     assert lv.liver_strerror(-1) == "invalid argument"                             # another code: no stale detail
     assert lv.liver_strerror(0) == "ok"
+
+
+def test_static_staging_entry_refuses_on_the_host_what_it_cannot_run():
+    """liver_reshard_static (for callers that cannot allocate): size limit and missing device are argument errors."""
+    assert lv.liver_static_staging_bytes() == 64 << 20
+    spec = lv.ModelSpec(n_layers=2, hidden=64, n_q_heads=4, n_kv_heads=4, ffn=128, vocab=64)
+    lay = lv.Layout(tp=1, pp=1, dp=1)
+    big = lv.liver_plan_create(spec, lv.Layout(tp=2, pp=1, dp=1), lay, (64 << 20) + 256)
+    try:
+        lv.liver_reshard_static(big, {}, {}, stream=0)
+        raise AssertionError("a chunk beyond the static array must be refused")
+    except lv.LiverError as e:
+        assert e.code == -1 and "exceeds the library's static staging array" in str(e) and "67108864" in str(e)
+    import torch
+    if not torch.cuda.is_available():
+        small = lv.liver_plan_create(spec, lv.Layout(tp=2, pp=1, dp=1), lay, 4096)
+        try:
+            lv.liver_reshard_static(small, {}, {}, stream=0)
+            raise AssertionError("a host-only plan cannot run")
+        except lv.LiverError as e:
+            assert e.code == -5
