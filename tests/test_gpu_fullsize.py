@@ -1,9 +1,12 @@
 """Parity at the full sizes of the large configurations, in the launch shape the
-benchmark times (library defaults): the state is generated in HBM, resharded by
-the HIP path (direct, then staged), and a sample of logical tensors -- first,
-middle and last layers, embeddings, head -- is gathered and re-split by the CPU
-oracle and compared bit for bit; plus size-independent properties (zero padding,
-untouched source)."""
+benchmark times (library defaults): the state is generated in HBM and resharded by
+the HIP path (direct, then staged).  For the three large benchmark configurations
+(7B, 13B share, 70B share) EVERY logical tensor is gathered and re-split by the CPU
+oracle, one group of tensors at a time, and every planned target element is compared
+bit for bit (LiveR, Section 6.6: element-wise comparison of the whole state, deviation
+exactly zero; Appendix A.2.1, Eq. 1); the variants of those configurations compare a
+sample of tensors -- first, middle and last layers, embeddings, head.  Plus
+size-independent properties (zero padding, untouched source)."""
 import numpy as np
 import pytest
 import torch
@@ -70,7 +73,7 @@ def _fresh_dst(plan, dst):
     return out
 
 
-def _expected(cfg, only, ospec, osrc, odst, src_bufs, names):
+def _expected(cfg, only, ospec, osrc, odst, src_bufs, names, quiet=False):
     """[(kind, tp, pp, stage_view, param, shard)] for the sampled tensors, from the oracle."""
     def read(rank, kind, lo, hi):
         if (rank, kind) not in src_bufs:                 # a source rank this filtered plan never reads
@@ -82,12 +85,13 @@ def _expected(cfg, only, ospec, osrc, odst, src_bufs, names):
     for k in cfg["kinds"]:
         logical = oracle.gather_logical(ospec, osrc, k, read, names=names)
         out += [(k,) + t for t in oracle.expected_shards(ospec, odst, logical, tps, pps)]
-        print(f"  oracle: kind {k} gathered and split", flush=True)
+        if not quiet:
+            print(f"  oracle: kind {k} gathered and split", flush=True)
     return out
 
 
-def _compare(expected, only, odst, dst_bufs, what):
-    n_checked = 0
+def _compare(expected, only, odst, dst_bufs, what, per_kind=False):
+    n_checked, by_kind = 0, {}
     for k, tp, pp, sv, prm, shard in expected:
         flat = shard.ravel()
         if k == 0:
@@ -100,8 +104,9 @@ def _compare(expected, only, odst, dst_bufs, what):
             got = dst_bufs[(odst.rank(tp, pp, d), k)][local:local + n].cpu().numpy().view(NP[k])
             assert np.array_equal(got, flat[at - prm.offset:at - prm.offset + n]), (what, prm.name, "dp", d, "kind", k)
             n_checked += n
+            by_kind[k] = by_kind.get(k, 0) + n
     assert n_checked > 0
-    return n_checked
+    return by_kind if per_kind else n_checked
 
 
 def _pads_zero(only, ospec, odst, dst_bufs):
@@ -120,6 +125,74 @@ def _pads_zero(only, ospec, odst, dst_bufs):
                 for dd, local, _, n in oracle.dp_pieces(sv, odst, used_end, b0 + nb):
                     if dd == d:
                         assert not t[local:local + n].any().item(), ("padding not zero", r, k)
+
+
+def _groups(ospec):
+    """All logical tensors in the groups the oracle handles one at a time: embeddings / final norm / head first,
+    then one transformer layer per group (host memory stays at one group)."""
+    import re
+    names = list(oracle.logical_tensors(ospec))
+    yield "embeddings, final norm, head", [n for n in names if not re.match(r"L\d+\.", n)]
+    for l in range(ospec.n_layers):
+        yield f"layer {l}", _layer(ospec, l)
+
+
+def _planned_bytes(cfg, only, ospec, odst, names):
+    """Bytes of planned target state built from `names` alone (0: the plan writes nothing that depends on them)."""
+    have, total = set(names), 0
+    for k in cfg["kinds"]:
+        for tp, pp, ep in oracle.columns(odst, k):
+            if only.get("tp", tp) != tp or only.get("pp", pp) != pp:
+                continue
+            sv = oracle.stage_view(ospec, odst, tp, pp, ep)
+            for prm in sv.params:
+                if not (prm.blocks and all(b.name in have for b in prm.blocks)):
+                    continue
+                if k == 0:
+                    total += 2 * prm.size * sum(1 for d in range(odst.dp) if only.get("dp", d) == d)
+                else:
+                    total += 4 * sum(n for d, _, _, n in oracle.dp_pieces(sv, odst, prm.offset, prm.offset + prm.size)
+                                     if only.get("dp", d) == d)
+    return total
+
+
+def _run_complete(name):
+    """Direct reshard compared with the oracle on EVERY planned target element, group by group; then the staged
+    path into a second set of target buffers, compared with the verified direct result on the device."""
+    import time
+    print(f"{name}: generating state in HBM", flush=True)
+    cfg, only, ospec, osrc, odst, plan, src, dst, src_bufs = _setup(name)
+    info = lv.liver_plan_info(plan)
+    sums = {key: int(t.view(torch.int16 if key[1] == 0 else torch.int32).sum(dtype=torch.int64)) for key, t in src_bufs.items()}
+    dst_bufs = _fresh_dst(plan, dst)
+    lv.liver_reshard(plan, src_bufs, dst_bufs)
+    torch.cuda.synchronize()
+    t0, n_bytes = time.perf_counter(), 0
+    for label, names in _groups(ospec):
+        want_bytes = _planned_bytes(cfg, only, ospec, odst, names)
+        if want_bytes == 0:
+            continue
+        expected = _expected(cfg, only, ospec, osrc, odst, src_bufs, names, quiet=True)
+        got_bytes = sum(n * (2 if k == 0 else 4) for k, n in _compare(expected, only, odst, dst_bufs, "direct", per_kind=True).items())
+        assert got_bytes == want_bytes, (label, got_bytes, want_bytes)
+        n_bytes += got_bytes
+        print(f"  {name}: {label} equal, {n_bytes / 1e9:.2f} GB so far, {time.perf_counter() - t0:.0f} s", flush=True)
+    _pads_zero(only, ospec, odst, dst_bufs)
+    # every byte the plan writes is either one of the compared elements or zero padding
+    assert n_bytes == info.bytes_written - info.pad_bytes == info.stream_bytes, (n_bytes, info.bytes_written, info.pad_bytes)
+    print(f"{name}: direct equals the oracle on all {n_bytes} bytes of planned target state "
+          f"(+ {info.pad_bytes} bytes of zero padding); staged path, {info.n_chunks} chunks", flush=True)
+    staged = _fresh_dst(plan, dst)
+    staging = torch.empty(cfg["chunk_bytes"], dtype=torch.uint8, device="cuda")
+    for c in range(info.n_chunks):
+        lv.liver_pack(plan, c, src_bufs, staging)
+        lv.liver_unpack(plan, c, staging, staged)
+    torch.cuda.synchronize()
+    for key in dst_bufs:
+        assert torch.equal(dst_bufs[key], staged[key]), ("staged differs from the verified direct result", key)
+    for key, t in src_bufs.items():          # source world untouched
+        assert int(t.view(torch.int16 if key[1] == 0 else torch.int32).sum(dtype=torch.int64)) == sums[key], key
+    print(f"{name}: staged ok (every element equal to the direct result)", flush=True)
 
 
 def _run(name, names):
@@ -155,24 +228,20 @@ def _layer(ospec, l, leaves=None):
     return [n for n in oracle.logical_tensors(ospec) if n.startswith(f"L{l}.") and (leaves is None or n.split(".", 1)[1] in leaves)]
 
 
-def test_llama7b_tp8_to_tp4pp2():
-    _, ospec, _, _ = cfg_objects("llama7b")
-    names = ["embed.word", "final_norm.w", "lm_head.w"] + _layer(ospec, 0) + _layer(ospec, 15, ("ln1.w", "q.w", "o.w", "down.w")) \
-        + _layer(ospec, 16, ("k.w", "v.w", "gate.w", "ln2.w")) + _layer(ospec, 31, ("o.w", "up.w", "down.w"))
-    _run("llama7b", names)
+def test_llama7b_tp8_to_tp4pp2_every_element():
+    """All 94,349,000,704 bytes of the 7B target state against the oracle."""
+    _run_complete("llama7b")
 
 
-def test_llama13b_dp8_to_dp6():
-    _, ospec, _, _ = cfg_objects("llama13b_dp")
-    # target rank (tp 0, pp 1, dp 2) owns flat elements of layers 26..30 of its stage
-    names = _layer(ospec, 26, ("o.w", "gate.w", "up.w", "down.w")) + _layer(ospec, 28) + _layer(ospec, 30, ("ln1.w", "q.w", "k.w", "v.w", "o.w"))
-    _run("llama13b_dp", names)
+def test_llama13b_dp8_to_dp6_every_element():
+    """The whole share of target rank (tp 0, pp 1, dp 2): 6.51 GB of fp32 optimizer state."""
+    _run_complete("llama13b_dp")
 
 
-def test_llama70b_one_target_rank():
-    _, ospec, _, _ = cfg_objects("llama70b_rank")
-    names = _layer(ospec, 30) + _layer(ospec, 39, ("q.w", "k.w", "v.w", "o.w", "ln2.w"))
-    _run("llama70b_rank", names)
+def test_llama70b_one_target_rank_every_element():
+    """The whole share of target rank (tp 1, pp 3, dp 2): bf16 weights of its 10 layers and its DP slice of the
+    fp32 state."""
+    _run_complete("llama70b_rank")
 
 
 def test_llama7b_layout_variants_at_full_size():
@@ -231,19 +300,17 @@ def test_llama7b_every_launch_shape_gives_the_same_bits():
         assert _digest(dst_bufs) == want, (grid, order, hints)
 
 
-def test_llama7b_round_trip_returns_every_bit():
-    """A -> B -> A at the full 7B size (fp32 kinds, 81 GB per world; a third world with the bf16 weights as well
-    would not fit).  The generated state has DIFFERENT values in the TP replicas of the norm weights, and a
-    gather reads replica 0, so: every buffer of TP rank 0 comes back bit for bit, the other ranks differ from
-    the original in at most the 65 replicated vectors, and from then on the state is a fixed point: a second
-    forward pass reproduces B exactly, and the staged path gives the same bits as the direct one."""
+def _round_trip_world(identical_replicas):
+    """The fp32 state of the 7B source world (81 GB; a third world with the bf16 weights as well would not fit),
+    both plans of the round trip, and the element ranges of the TP-replicated parameters on TP ranks > 0."""
     cfg = dict(synth.CONFIGS["llama7b"], kinds=(1, 2, 3))
+    ospec = oracle.ModelSpec(**cfg["spec"])
+    osrc = oracle.Layout(pad_multiple=cfg["pad_multiple"], **cfg["src"])
     spec = lv.ModelSpec(**cfg["spec"])
     a = dict(pad_multiple=cfg["pad_multiple"], **cfg["src"])
     b = dict(pad_multiple=cfg["pad_multiple"], **cfg["dst"])
     fwd = lv.liver_plan_create(spec, lv.Layout(**a), lv.Layout(kinds=(1, 2, 3), **b), cfg["chunk_bytes"])
     back = lv.liver_plan_create(spec, lv.Layout(**b), lv.Layout(kinds=(1, 2, 3), **a), cfg["chunk_bytes"])
-    print("round trip: generating state in HBM", flush=True)
     g = torch.Generator(device="cuda").manual_seed(synth.SEED_BASE)
     A = {}
     for r in range(fwd.src.n_ranks):
@@ -251,6 +318,28 @@ def test_llama7b_round_trip_returns_every_bit():
             n = lv.liver_plan_buffer_bytes(fwd, 0, r, k) // 4
             assert n == lv.liver_plan_buffer_bytes(back, 1, r, k) // 4
             A[(r, k)] = torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, 0.02, generator=g).view(torch.int32)
+    assert osrc.dp == 1 and osrc.pp == 1                     # flat offsets are buffer offsets in this world
+    first = {p.name: p for p in oracle.stage_view(ospec, osrc, 0, 0).params}
+    copies = []                                              # (tp, offset there, offset on tp 0, elements)
+    for tp in range(1, osrc.tp):
+        for p in oracle.stage_view(ospec, osrc, tp, 0).params:
+            if not p.canonical:
+                assert first[p.name].size == p.size
+                copies.append((tp, p.offset, first[p.name].offset, p.size))
+    assert len(copies) == (osrc.tp - 1) * (2 * ospec.n_layers + 1)      # ln1.w, ln2.w per layer, final_norm.w
+    if identical_replicas:                                   # what a real training job holds: replicas agree
+        for tp, off, off0, n in copies:
+            for k in (1, 2, 3):
+                A[(osrc.rank(tp, 0, 0), k)][off:off + n] = A[(osrc.rank(0, 0, 0), k)][off0:off0 + n]
+    return cfg, fwd, back, A, copies, osrc
+
+
+def test_llama7b_round_trip_returns_every_bit():
+    """A -> B -> A at the full 7B size with identical TP replicas of the replicated parameters (the precondition
+    under which a round trip is the identity): EVERY buffer of every rank comes back bit for bit.  A second
+    forward pass through the staged path reproduces B exactly."""
+    print("round trip: generating state in HBM", flush=True)
+    cfg, fwd, back, A, _, _ = _round_trip_world(identical_replicas=True)
     B = _fresh_dst(fwd, fwd.dst)
     print("round trip: forward", flush=True)
     lv.liver_reshard(fwd, A, B)
@@ -259,10 +348,8 @@ def test_llama7b_round_trip_returns_every_bit():
     lv.liver_reshard(back, B, A2)
     torch.cuda.synchronize()
     assert set(A2) == set(A)
-    replicated = (2 * spec.n_layers + 1) * spec.hidden         # ln1.w, ln2.w per layer, final_norm.w
-    for (r, k), t in A.items():
-        differ = int((t != A2[(r, k)]).sum())
-        assert differ == 0 if r == 0 else 0 < differ <= replicated, (r, k, differ)
+    for key, t in A.items():
+        assert torch.equal(t, A2[key]), key
     del A, t
     print("round trip: second forward pass, staged", flush=True)
     B2 = _fresh_dst(fwd, fwd.dst)
@@ -273,6 +360,30 @@ def test_llama7b_round_trip_returns_every_bit():
     torch.cuda.synchronize()
     for key in B:
         assert torch.equal(B[key], B2[key]), key
+
+
+def test_llama7b_reads_only_the_first_replica():
+    """Which copy of a replicated value is read, at full size: with DIFFERENT values in the TP replicas of the
+    norm weights the target world is the same as with the replicas of TP rank 0 everywhere, and the way back
+    writes TP rank 0's values into every replica."""
+    print("first replica: generating state in HBM", flush=True)
+    cfg, fwd, back, A, copies, osrc = _round_trip_world(identical_replicas=False)
+    B = _fresh_dst(fwd, fwd.dst)
+    lv.liver_reshard(fwd, A, B)
+    A2 = _fresh_dst(back, back.dst)
+    lv.liver_reshard(back, B, A2)
+    torch.cuda.synchronize()
+    print("first replica: comparing", flush=True)
+    for k in (1, 2, 3):
+        r0 = osrc.rank(0, 0, 0)
+        assert torch.equal(A[(r0, k)], A2[(r0, k)]), k
+        for tp, off, off0, n in copies:
+            r = osrc.rank(tp, 0, 0)
+            assert not torch.equal(A[(r, k)][off:off + n], A[(r0, k)][off0:off0 + n])         # the input replicas differ
+            assert torch.equal(A2[(r, k)][off:off + n], A[(r0, k)][off0:off0 + n]), (tp, off, k)
+            A[(r, k)][off:off + n] = A[(r0, k)][off0:off0 + n]
+    for key, t in A.items():          # apart from the replicas, nothing changed on the way there and back
+        assert torch.equal(t, A2[key]), key
 
 
 def test_llama13b_through_a_5_gib_staging_chunk():
