@@ -229,11 +229,12 @@ int liver_plan_desc(const liver_plan_t* plan, int list, int64_t i, liver_desc_t*
 /* Launch shape of the copy kernels (a tuning knob of this implementation; the paper has no counterpart).
  * A plan is immutable and may be used from several threads and streams at once, with ONE exception: this
  * call, which is meant for the time between liver_plan_create and the plan's first data call.
- * grid_blocks workgroups of 256 threads
- * (0 = default: one per compute unit); tile_order 0 = each workgroup walks one
- * contiguous range of tiles, 1 = workgroups interleave tile by tile, 2 = groups
- * of up to 64 tiles visited in a scattered (multiplicative-permutation) order,
- * -1 = default (contiguous);
+ * grid_blocks workgroups of 256 threads (0 = default: one per compute unit);
+ * tile_order 0 = each workgroup walks one contiguous range of tiles, 1 = workgroups interleave tile by tile,
+ * 2 = groups of up to 64 tiles visited in a scattered (multiplicative-permutation) order, 3 = teams: 8 or 32
+ * workgroups (by launch size) share one contiguous range and interleave inside it, a team's members sitting on
+ * one XCD; 100 + w = teams of w workgroups (2 <= w <= 1024; the grid is rounded down to a multiple of w, and a
+ * launch with fewer than 8 teams runs as order 0); -1 = default (teams);
  * cache_hints bit 0 = non-temporal loads, bit 1 = non-temporal stores, -1 =
  * default (direct: both; pack: loads only; unpack: stores only, so that the
  * staging chunk may stay cache-resident).  Not thread-safe against concurrent
@@ -271,6 +272,17 @@ int liver_reshard(const liver_plan_t* plan, const void* const* src_bufs, void* c
  * first kernel is enqueued, so an argument error writes nothing. */
 int liver_reshard_staged(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs,
                          void* const* staging, int n_staging, void* stream_pack, void* stream_unpack);
+
+/* The staged reshard on ONE stream with half the launches: launch k runs the unpack of chunk k-1 (out of one
+ * staging chunk) and the pack of chunk k (into the other) as one grid, so the tail of each kernel is covered
+ * by the head of the next (the layer-by-layer receive / assemble / send-next overlap of Algorithm 1 and the
+ * pipelined chunk transfer of Section 5, folded into single launches).  Chunk k goes through staging_even if k
+ * is even, staging_odd if odd (device, chunk_bytes each, 256 B aligned, distinct).  n_chunks + 1 launches in
+ * all; same target bytes as liver_pack + liver_unpack, bit for bit.  Chunks that need more than one pass on
+ * either side, and plans with a non-default launch shape, fall back to separate launches for that step.
+ * Allocates nothing, does not synchronise; every buffer is validated before the first launch. */
+int liver_reshard_staged_fused(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs,
+                               void* staging_even, void* staging_odd, void* hip_stream);
 
 /* For callers that cannot allocate device memory at all -- code under HIP-graph capture, tight serving
  * loops, harnesses that forbid hipMalloc: the whole staged reshard (pack and unpack of every chunk, in order,

@@ -135,6 +135,7 @@ def _load() -> C.CDLL:
     lib.liver_unpack.argtypes = [P, C.c_int, P, C.POINTER(P), P]
     lib.liver_reshard.argtypes = [P, C.POINTER(P), C.POINTER(P), P]
     lib.liver_reshard_staged.argtypes = [P, C.POINTER(P), C.POINTER(P), C.POINTER(P), C.c_int, P, P]
+    lib.liver_reshard_staged_fused.argtypes = [P, C.POINTER(P), C.POINTER(P), P, P, P]
     lib.liver_reshard_static.argtypes = [P, C.POINTER(P), C.POINTER(P), P]
     lib.liver_static_staging_bytes.argtypes = []
     lib.liver_static_staging_bytes.restype = C.c_size_t
@@ -287,6 +288,13 @@ def liver_reshard_staged(plan: Plan, src_bufs, dst_bufs, staging, stream_pack=No
     _check(_lib.liver_reshard_staged(plan.handle, _table(src_bufs, plan.src.n_ranks, plan, 0),
                                      _table(dst_bufs, plan.dst.n_ranks, plan, 1),
                                      arr, len(staging), _stream(stream_pack), _stream(stream_unpack)))
+
+
+def liver_reshard_staged_fused(plan: Plan, src_bufs, dst_bufs, staging_even, staging_odd, stream=None) -> None:
+    _check(_lib.liver_reshard_staged_fused(plan.handle, _table(src_bufs, plan.src.n_ranks, plan, 0),
+                                           _table(dst_bufs, plan.dst.n_ranks, plan, 1),
+                                           _checked(staging_even, plan.chunk_bytes, "staging chunk"),
+                                           _checked(staging_odd, plan.chunk_bytes, "staging chunk"), _stream(stream)))
 
 
 def liver_reshard_static(plan: Plan, src_bufs, dst_bufs, stream=None) -> None:

@@ -1,4 +1,5 @@
-"""Builds libliver.so (HIP kernels + host planner + C ABI) for gfx950, in-tree."""
+"""Builds libliver.so (HIP kernels + host planner + C ABI) and the placement_probe measurement program for
+gfx950, in-tree."""
 import os
 import subprocess
 import sys
@@ -6,6 +7,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libliver.so")
+PROBE = os.path.join(HERE, "placement_probe")
 SOURCES = ["planner.cpp", "api.cpp", "emulate.cpp", "kernels.hip", "static_staging.hip"]
 
 
@@ -20,6 +22,15 @@ def build(verbose: bool = False) -> str:
         sys.stderr.write(res.stdout + res.stderr)
     if res.returncode:
         raise RuntimeError("hipcc failed building libliver.so")
+    # the stand-alone measurement program (placement of buffers in HBM vs streaming bandwidth)
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-o", PROBE, os.path.join(HERE, "csrc", "placement_probe.hip")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode:
+        sys.stderr.write(res.stdout + res.stderr)
+    if res.returncode:
+        raise RuntimeError("hipcc failed building placement_probe")
     return LIB
 
 

@@ -58,11 +58,16 @@ int launch_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, 
         args.descs = (const liver::DevDesc*)((const char*)plan->dev_table + list.dev_offset) + pass.desc_begin;
         args.n_desc = pass.desc_count;
         args.n_tiles = pass.n_tiles;
-        // Tile order: one contiguous tile range per workgroup is the default.  Measured on MI355X it wins
-        // whenever the buffers are spread over the HBM (7B direct: 6.2 vs 5.9 TB/s; 13B share: 6.3 vs 5.7) and
-        // for the chunk-sized pack / unpack launches; tile-by-tile interleaving only wins (4-8 %) for
-        // launches of a few GB whose buffers all sit next to each other.
-        args.tile_order = plan->tile_order >= 0 ? (uint32_t)plan->tile_order : 0u;
+        uint32_t grid = pass.n_tiles < max_grid ? pass.n_tiles : max_grid;
+        // Tile order.  Default (-1) and order 3: TEAMS.  `width` workgroups share one contiguous tile range and
+        // interleave tile by tile inside it; team = workgroup id mod team count, so with a team count that is a
+        // multiple of 8 a team's members all sit on one XCD and its stream stays in that XCD's L2.  Measured on
+        // MI355X against one range per workgroup (order 0): 7B +0..1 %, 13B share +3..6 %, 70B share +1..2 %,
+        // GPT-2-small +-0.5 %; all 256 workgroups interleaving (order 1) loses 4..9 % except when every buffer
+        // sits in one 32 GiB region of the HBM.  Big launches run best as 32 teams of 8, small ones as 8 teams
+        // (one per XCD) of 32.  100 + w = teams of w (tuning aid).
+        const int order = plan->tile_order < 0 ? 3 : plan->tile_order;
+        args.tile_order = order >= 3 ? 0u : (uint32_t)order;
         args.reserved = 0;
         // scattered order: groups of up to 64 tiles (4 MiB), at least ~32 groups per workgroup; the groups
         // are visited in a multiplicative permutation with a multiplier near 0.618 * n_groups
@@ -76,10 +81,16 @@ int launch_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, 
             if (mul < 1 || n_groups < 3) mul = 1;
             args.group = group, args.perm_mul = mul;
         }
+        if (order >= 3) {
+            const uint32_t width = order >= 100 ? (uint32_t)order - 100u : pass.n_tiles >= (1u << 20) ? 8u : 32u;
+            if (width >= 2 && grid / width >= 8) {  // else: too few workgroups for teams, one range each (order 0)
+                grid -= grid % width;
+                args.tile_order = 3, args.group = width;
+            }
+        }
         size_t i = 0;
         for (const liver::BufRef& r : pass.bufs) args.bufs[i++] = (char*)resolve(r, src_bufs, dst_bufs, staging);
         for (; i < (size_t)liver::MAX_PASS_BUFS; ++i) args.bufs[i] = nullptr;
-        const uint32_t grid = pass.n_tiles < max_grid ? pass.n_tiles : max_grid;
         hipError_t e = liver::launch_pass(args, grid, hints, (hipStream_t)hip_stream);
         if (e != hipSuccess) return fail(LIVER_E_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
     }
@@ -199,7 +210,7 @@ int liver_plan_desc(const liver_plan_t* plan, int list, int64_t i, liver_desc_t*
 }
 
 int liver_plan_set_launch(liver_plan_t* plan, int grid_blocks, int tile_order, int cache_hints) {
-    if (!plan || grid_blocks < 0 || grid_blocks > 65536 || tile_order < -1 || tile_order > 2 || cache_hints < -1 ||
+    if (!plan || grid_blocks < 0 || grid_blocks > 65536 || tile_order < -1 || (tile_order > 3 && (tile_order < 102 || tile_order > 1124)) || cache_hints < -1 ||
         cache_hints > 3)
         return fail(LIVER_E_INVALID_ARG, "bad launch shape");
     plan->grid_blocks = grid_blocks, plan->tile_order = tile_order, plan->cache_hints = cache_hints;
@@ -273,6 +284,58 @@ int liver_reshard_staged(const liver_plan_t* plan, const void* const* src_bufs, 
     if (rc != LIVER_OK) return rc;  // a launch the runtime refused (LIVER_E_HIP): earlier chunks may have run
     if (e != hipSuccess) return fail(LIVER_E_HIP, std::string("staged pipeline: ") + hipGetErrorString(e));
     return LIVER_OK;
+}
+
+int liver_reshard_staged_fused(const liver_plan_t* plan, const void* const* src_bufs, void* const* dst_bufs,
+                               void* staging_even, void* staging_odd, void* hip_stream) {
+    if (!plan || !src_bufs || !dst_bufs || !staging_even || !staging_odd) return fail(LIVER_E_INVALID_ARG, "null argument");
+    if ((uintptr_t)staging_even % 256 || (uintptr_t)staging_odd % 256)
+        return fail(LIVER_E_INVALID_ARG, "staging chunks must be 256-byte aligned");
+    if (staging_even == staging_odd) return fail(LIVER_E_INVALID_ARG, "staging chunks must be distinct");
+    void* const slot[2] = {staging_even, staging_odd};
+    const liver::List &pk = plan->pack, &un = plan->unpack;
+    // every chunk's buffers are checked before the first kernel is enqueued: an argument error writes nothing
+    int rc = check_passes(plan, pk, 0, (uint32_t)pk.passes.size(), src_bufs, nullptr, staging_even);
+    if (rc == LIVER_OK) rc = check_passes(plan, un, 0, (uint32_t)un.passes.size(), nullptr, dst_bufs, staging_even);
+    if (rc != LIVER_OK) return rc;
+    const int n_chunks = (int)plan->info.n_chunks;
+    const uint32_t max_grid = plan->grid_blocks > 0 ? (uint32_t)plan->grid_blocks : (uint32_t)plan->n_cu;
+    // launch k = unpack(k - 1) + pack(k): chunk k - 1 leaves its staging chunk while chunk k enters the other one
+    for (int k = 0; k <= n_chunks && rc == LIVER_OK; ++k) {
+        const bool has_un = k > 0, has_pk = k < n_chunks;
+        const uint32_t u0 = has_un ? un.chunk_pass[k - 1] : 0, u1 = has_un ? un.chunk_pass[k] : 0;
+        const uint32_t p0 = has_pk ? pk.chunk_pass[k] : 0, p1 = has_pk ? pk.chunk_pass[k + 1] : 0;
+        void* s_un = slot[(k + 1) & 1];  // chunk k - 1
+        void* s_pk = slot[k & 1];        // chunk k
+        const liver::Pass* a = u1 - u0 == 1 ? &un.passes[u0] : nullptr;
+        const liver::Pass* b = p1 - p0 == 1 ? &pk.passes[p0] : nullptr;
+        const bool fuse = a && b && a->n_tiles > 0 && b->n_tiles > 0 && plan->cache_hints < 0 && plan->tile_order < 0 &&
+                          a->bufs.size() + b->bufs.size() <= (size_t)liver::MAX_PASS_BUFS &&
+                          (uint64_t)a->n_tiles + b->n_tiles < (1u << 31);
+        if (!fuse) {  // a chunk that needs several passes, an empty side, or a non-default launch shape: one after the other
+            if (has_un) rc = launch_passes(plan, un, u0, u1, nullptr, dst_bufs, s_un, hip_stream, HINT_UNPACK);
+            if (rc == LIVER_OK && has_pk) rc = launch_passes(plan, pk, p0, p1, src_bufs, nullptr, s_pk, hip_stream, HINT_PACK);
+            continue;
+        }
+        liver::FusedArgs args;
+        size_t i = 0;
+        const liver::Pass* pass[2] = {a, b};
+        const liver::List* list[2] = {&un, &pk};
+        void* stage[2] = {s_un, s_pk};
+        for (int g = 0; g < 2; ++g) {
+            args.seg[g].descs = (const liver::DevDesc*)((const char*)plan->dev_table + list[g]->dev_offset) + pass[g]->desc_begin;
+            args.seg[g].n_desc = pass[g]->desc_count;
+            args.seg[g].n_tiles = pass[g]->n_tiles;
+            args.seg[g].buf_base = (uint32_t)i;
+            args.seg[g].reserved = 0;
+            for (const liver::BufRef& r : pass[g]->bufs) args.bufs[i++] = (char*)resolve(r, src_bufs, dst_bufs, stage[g]);
+        }
+        for (; i < (size_t)liver::MAX_PASS_BUFS; ++i) args.bufs[i] = nullptr;
+        const uint32_t total = a->n_tiles + b->n_tiles;
+        const hipError_t e = liver::launch_fused(args, total < max_grid ? total : max_grid, (hipStream_t)hip_stream);
+        if (e != hipSuccess) rc = fail(LIVER_E_HIP, std::string("kernel launch: ") + hipGetErrorString(e));
+    }
+    return rc;
 }
 
 size_t liver_static_staging_bytes(void) { return liver::STATIC_STAGING_BYTES; }

@@ -147,8 +147,15 @@ __device__ __forceinline__ void tile_zero(uint32_t u0, uint32_t n, char* b) {
 
 // Everything one workgroup does for tiles [t, t_end) with stride `step`: find the descriptor of the
 // first tile (binary search), then walk forward through the descriptor table.
+// A descriptor range with its tiles and the buffer table its descriptors index into.
+struct TileSet {
+    const DevDesc* descs;
+    uint32_t n_desc, n_tiles;
+    char* const* bufs;
+};
+
 template <class M>
-__device__ __forceinline__ void run_tiles(const PassArgs& args, uint32_t t, uint32_t t_end, uint32_t step) {
+__device__ __forceinline__ void run_tiles(const TileSet& args, uint32_t t, uint32_t t_end, uint32_t step) {
     const uint32_t n_tiles = args.n_tiles;
     const DevDesc* __restrict__ descs = args.descs;
     // last descriptor whose first tile is <= t  (descs[0].tile_begin == 0)
@@ -189,24 +196,53 @@ __device__ __forceinline__ void run_tiles(const PassArgs& args, uint32_t t, uint
 }
 
 template <bool NTL, bool NTS>
-__global__ __launch_bounds__(BLOCK) void liver_copy_kernel(const PassArgs args) {
+__global__ __launch_bounds__(BLOCK) void liver_copy_kernel(const PassArgs pass) {
     typedef Mem<NTL, NTS> M;
-    const uint32_t n_tiles = args.n_tiles, G = gridDim.x, w = blockIdx.x;
-    if (args.tile_order == 0) {         // one contiguous range of tiles per workgroup
+    const TileSet args{pass.descs, pass.n_desc, pass.n_tiles, pass.bufs};
+    const uint32_t n_tiles = pass.n_tiles, G = gridDim.x, w = blockIdx.x;
+    if (pass.tile_order == 0) {         // one contiguous range of tiles per workgroup
         const uint32_t per = (n_tiles + G - 1) / G;
         const uint32_t t = w * per;     // below 2^32: n_tiles < 2^31 and G <= n_tiles (host checks)
         if (t < n_tiles) run_tiles<M>(args, t, t + per < n_tiles ? t + per : n_tiles, 1);
-    } else if (args.tile_order == 1) {  // workgroups interleave tile by tile
+    } else if (pass.tile_order == 1) {  // workgroups interleave tile by tile
         if (w < n_tiles) run_tiles<M>(args, w, n_tiles, G);
+    } else if (pass.tile_order == 3) {  // teams: `group` workgroups share one contiguous range and interleave tile by
+                                        // tile inside it; team = w mod n_teams, so a team's members sit on one XCD
+        const uint32_t width = pass.group, n_teams = G / width;   // host: G is a multiple of width
+        const uint32_t team = w % n_teams, member = w / n_teams;
+        const uint32_t per = (n_tiles + n_teams - 1) / n_teams;
+        const uint32_t t0 = team * per, t1 = t0 + per < n_tiles ? t0 + per : n_tiles;
+        if (t0 + member < t1) run_tiles<M>(args, t0 + member, t1, width);
     } else {                            // scattered: groups of `group` consecutive tiles, visited in the order
                                         // i -> (i * perm_mul) mod n_groups (perm_mul coprime to n_groups)
-        const uint32_t group = args.group, n_groups = (n_tiles + group - 1) / group;
+        const uint32_t group = pass.group, n_groups = (n_tiles + group - 1) / group;
         for (uint32_t i = w; i < n_groups; i += G) {
-            const uint32_t gi = (uint32_t)(((uint64_t)i * args.perm_mul) % n_groups);
+            const uint32_t gi = (uint32_t)(((uint64_t)i * pass.perm_mul) % n_groups);
             const uint32_t t = gi * group;
             run_tiles<M>(args, t, t + group < n_tiles ? t + group : n_tiles, 1);
         }
     }
+}
+
+template <int HINTS>
+__device__ __forceinline__ void run_segment(const FusedArgs& f, int i, uint32_t t, uint32_t t_end) {
+    const TileSet ts{f.seg[i].descs, f.seg[i].n_desc, f.seg[i].n_tiles, f.bufs + f.seg[i].buf_base};
+    run_tiles<Mem<(HINTS & 1) != 0, (HINTS & 2) != 0>>(ts, t, t_end, 1);
+}
+
+// Two descriptor ranges in one launch, each with its own cache policy: the staged pipeline's unpack of chunk
+// k-1 (segment 0) and pack of chunk k (segment 1), which touch different staging chunks and are independent.
+// The tiles of both are numbered through; each workgroup takes one contiguous range of them, so the tail of
+// one segment and the head of the other are covered by the same full grid.
+template <int HINTS0, int HINTS1>
+__global__ __launch_bounds__(BLOCK) void liver_fused_kernel(const FusedArgs f) {
+    const uint32_t n0 = f.seg[0].n_tiles, total = n0 + f.seg[1].n_tiles, G = gridDim.x, w = blockIdx.x;
+    const uint32_t per = (total + G - 1) / G;
+    const uint32_t t0 = w * per;  // below 2^32: total < 2^31 and G <= total (host checks)
+    if (t0 >= total) return;
+    const uint32_t t1 = t0 + per < total ? t0 + per : total;
+    if (t0 < n0) run_segment<HINTS0>(f, 0, t0, t1 < n0 ? t1 : n0);
+    if (t1 > n0) run_segment<HINTS1>(f, 1, (t0 > n0 ? t0 : n0) - n0, t1 - n0);
 }
 
 }  // namespace
@@ -257,6 +293,13 @@ hipError_t launch_pass(const PassArgs& args, uint32_t grid, int cache_hints, hip
         default: fn = (const void*)&liver_copy_kernel<true, true>; break;
     }
     return hipLaunchKernel(fn, dim3(grid), dim3(BLOCK), kargs, 0, stream);
+}
+
+hipError_t launch_fused(const FusedArgs& args, uint32_t grid, hipStream_t stream) {
+    void* kargs[] = {(void*)&args};
+    // segment 0 scatters a staging chunk (just written: plain loads) into targets that are streamed (non-temporal
+    // stores); segment 1 gathers streamed sources (non-temporal loads) into a staging chunk that is re-read at once
+    return hipLaunchKernel((const void*)&liver_fused_kernel<2, 1>, dim3(grid), dim3(BLOCK), kargs, 0, stream);
 }
 
 }  // namespace liver

@@ -20,6 +20,23 @@ struct PassArgs {
 };
 static_assert(sizeof(PassArgs) <= 3584, "kernel arguments must fit the kernarg segment");
 
+// Arguments of a fused launch: two descriptor ranges (segments) whose tiles are numbered through; the
+// descriptors of segment i index bufs[buf_base + ...].
+struct FusedArgs {
+    struct Segment {
+        const DevDesc* descs;
+        uint32_t n_desc;
+        uint32_t n_tiles;
+        uint32_t buf_base;
+        uint32_t reserved;
+    } seg[2];
+    char* bufs[MAX_PASS_BUFS];
+};
+static_assert(sizeof(FusedArgs) <= 3584, "kernel arguments must fit the kernarg segment");
+// Enqueue both segments in one launch (unpack policy for segment 0, pack policy for segment 1);
+// 1 <= grid <= seg[0].n_tiles + seg[1].n_tiles, both segments non-empty.
+hipError_t launch_fused(const FusedArgs& args, uint32_t grid, hipStream_t stream);
+
 // Enqueue one pass on `stream` with `grid` workgroups (1 <= grid <= n_tiles).
 hipError_t launch_pass(const PassArgs& args, uint32_t grid, int cache_hints, hipStream_t stream);
 

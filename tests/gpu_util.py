@@ -50,6 +50,16 @@ def run_staged(plan, src_dev, order=None, only_used=False):
     return dst
 
 
+def run_fused(plan, src_dev, only_used=False):
+    """The staged reshard with unpack(k-1) and pack(k) fused into one launch, through two staging chunks."""
+    dst = alloc_dst(plan, only_used)
+    a = torch.full((plan.chunk_bytes,), 0x3C, dtype=torch.uint8, device="cuda")
+    b = torch.full((plan.chunk_bytes,), 0xC3, dtype=torch.uint8, device="cuda")
+    lv.liver_reshard_staged_fused(plan, src_dev, dst, a, b)
+    torch.cuda.synchronize()
+    return dst
+
+
 def check_against(got_dev, want, plan, what=""):
     """Planned buffers equal the oracle's; unplanned ones still hold the sentinel."""
     got = to_host(got_dev)

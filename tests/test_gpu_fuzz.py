@@ -14,7 +14,7 @@ import oracle
 import paper_2605_22014_amd as lv
 from interp import lv_objects, emulate_direct, emulate_staged, used_dst
 from util import make_world, tiny_state, corrupt_replicas
-from gpu_util import to_dev, run_direct, run_staged, check_against
+from gpu_util import to_dev, run_direct, run_staged, run_fused, check_against
 from test_planner_fuzz import layouts
 
 pytestmark = pytest.mark.gpu
@@ -69,4 +69,5 @@ def test_random_worlds_on_device(case):
     dev = to_dev(world)
     check_against(run_direct(plan, dev), want, plan, "direct")
     check_against(run_staged(plan, dev), want, plan, "staged")
+    check_against(run_fused(plan, dev), want, plan, "staged, fused launches")
     lv.liver_plan_destroy(plan)

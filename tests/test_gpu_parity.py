@@ -9,7 +9,7 @@ import oracle
 import paper_2605_22014_amd as lv
 from interp import lv_objects
 from util import cfg_objects, make_world, tiny_state, corrupt_replicas
-from gpu_util import to_dev, to_host, run_direct, run_staged, check_against, alloc_dst
+from gpu_util import to_dev, to_host, run_direct, run_staged, run_fused, check_against, alloc_dst
 from test_oracle_reshard import ODD, BRUTE
 from test_planner_host import FILTERS
 
@@ -220,6 +220,54 @@ def test_pipelined_staged_reshard(gpt2, n_staging, two_streams):
     check_against(out, want, plan, "pipelined staged")
     with pytest.raises(lv.LiverError):
         lv.liver_reshard_staged(plan, dev, out, [staging[0], staging[0]])
+
+
+@pytest.mark.parametrize("chunk_bytes", [16 << 20, 64 << 20, 3 << 30])
+def test_fused_staged_reshard(gpt2, chunk_bytes):
+    """liver_reshard_staged_fused: unpack(k-1) and pack(k) in one launch; 122, 31 and 1 chunk(s)."""
+    cfg, spec, src, dst, world, want, dev = gpt2
+    print(f"gpt2_small fused staged, chunk {chunk_bytes}", flush=True)
+    plan = _plan(spec, src, dst, chunk_bytes)
+    check_against(run_fused(plan, dev), want, plan, "fused staged")
+    if chunk_bytes == 16 << 20:
+        out = alloc_dst(plan)
+        a = torch.empty(chunk_bytes, dtype=torch.uint8, device="cuda")
+        keep = {k: t.clone() for k, t in out.items()}
+        with pytest.raises(lv.LiverError):
+            lv.liver_reshard_staged_fused(plan, dev, out, a, a)                      # the two chunks must differ
+        missing = dict(dev)
+        missing[max(k for k in missing if k[1] == lv.ADAM_V)] = None                 # read by the last chunks only
+        with pytest.raises(lv.LiverError, match="NULL"):
+            lv.liver_reshard_staged_fused(plan, missing, out, a, torch.empty_like(a))
+        torch.cuda.synchronize()
+        for k in keep:
+            assert torch.equal(keep[k], out[k]), k                                    # refused before any launch
+        lv.liver_plan_set_launch(plan, 512, 1, 3)       # a non-default launch shape takes the unfused path of the same entry
+        check_against(run_fused(plan, dev), want, plan, "fused entry, non-default launch shape")
+
+
+@pytest.mark.parametrize("derive", [False, True])
+def test_fused_staged_reshard_small_and_odd(derive):
+    """Chunks of a few KiB (hundreds of launches, partial tiles, element paths), filtered plans, derive mode."""
+    cfg, spec, src, dst = cfg_objects("tiny_gpt")
+    print(f"tiny_gpt fused staged derive {derive}", flush=True)
+    world = make_world(spec, src, synth.logical_state(oracle.logical_tensors(spec), 11, cfg["dist"]))
+    want = oracle.reshard_state(spec, src, dst, world, derive_bf16=derive)
+    dev = to_dev(world)
+    for cb in (4096, 65536, 1 << 20):
+        plan = _plan(spec, src, dst, cb, derive)
+        check_against(run_fused(plan, dev), want, plan, f"fused staged {cb}")
+    for case in (3, 8, 17):
+        ospec, s, d = BRUTE[case]
+        osrc, odst = oracle.Layout(*s), oracle.Layout(*d)
+        w = make_world(ospec, osrc, tiny_state(ospec, seed=case))
+        plan = _plan(ospec, osrc, odst, 512, derive)
+        check_against(run_fused(plan, to_dev(w)), oracle.reshard_state(ospec, osrc, odst, w, derive_bf16=derive), plan, f"fused odd {case}")
+    f = FILTERS[1]
+    osrc, odst = oracle.Layout(1, 2, 2, 4), oracle.Layout(2, 2, 3, 1)
+    w = make_world(ODD, osrc, tiny_state(ODD, seed=41))
+    plan = _plan(ODD, osrc, odst, 512, derive, **f)
+    check_against(run_fused(plan, to_dev(w)), oracle.reshard_state(ODD, osrc, odst, w, derive_bf16=derive), plan, "fused filtered")
 
 
 def test_identity_layout_is_a_plain_copy():
