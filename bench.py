@@ -123,33 +123,28 @@ class World:
         src_keys = [(r, k) for r in range(src.n_ranks) for k in range(4) if k in cfg["kinds"] and _column_used(lv, plan, src, r)]
         dst_keys = [(r, k) for r in range(dst.n_ranks) for k in range(4) if lv.liver_plan_buffer_used(plan, 1, r, k)]
 
-        def alloc(side, r, k):
-            n = lv.liver_plan_buffer_bytes(plan, side, r, k)
-            if side == 1:
-                return torch.empty(n, dtype=torch.uint8, device="cuda")
-            return torch.empty(n // (2 if k == 0 else 4), dtype=torch.bfloat16 if k == 0 else torch.float32, device="cuda")
-        self.src_bufs, self.dst_bufs, self.gaps = {}, {}, []
+        def view(t, side, k):
+            return t if side == 1 else t.view(torch.bfloat16 if k == 0 else torch.float32)
+        size = lambda side, key: lv.liver_plan_buffer_bytes(plan, side, *key)
+        self.src_bufs, self.dst_bufs = {}, {}
         if placement == "natural":
             # what a training framework does: every source buffer, then every target buffer, back to back
-            for r, k in src_keys:
-                self.src_bufs[(r, k)] = alloc(0, r, k)
-            for r, k in dst_keys:
-                self.dst_bufs[(r, k)] = alloc(1, r, k)
+            for side, keys, bufs in ((0, src_keys, self.src_bufs), (1, dst_keys, self.dst_bufs)):
+                for key in keys:
+                    bufs[key] = view(torch.empty(size(side, key), dtype=torch.uint8, device="cuda"), side, key[1])
             self.placement = "all source buffers, then all target buffers, in plain allocation order (no gaps)"
         else:
-            # source and target buffers allocated ALTERNATELY and SPREAD over the whole HBM by unused gap
-            # allocations between them
-            need = sum(lv.liver_plan_buffer_bytes(plan, 0, r, k) for r, k in src_keys) \
-                + sum(lv.liver_plan_buffer_bytes(plan, 1, r, k) for r, k in dst_keys)
-            free, _ = torch.cuda.mem_get_info()
-            gap = max(0, (free - need - (14 << 30)) // (len(src_keys) + len(dst_keys))) & ~((2 << 20) - 1)
+            # source and target buffers allocated ALTERNATELY and strided over the whole free HBM by temporary
+            # spacer allocations (released again before the first launch): paper_2605_22014_amd.placement
+            order = []
             for i in range(max(len(src_keys), len(dst_keys))):
-                for side, keys, bufs in ((0, src_keys, self.src_bufs), (1, dst_keys, self.dst_bufs)):
-                    if i < len(keys):
-                        bufs[keys[i]] = alloc(side, *keys[i])
-                        if gap:
-                            self.gaps.append(torch.empty(gap, dtype=torch.uint8, device="cuda"))
-            self.placement = f"source/target buffers allocated alternately, {gap >> 20} MiB unused gap after each"
+                order += [(0, src_keys[i])] if i < len(src_keys) else []
+                order += [(1, dst_keys[i])] if i < len(dst_keys) else []
+            from paper_2605_22014_amd.placement import alloc_spread
+            for (side, key), t in zip(order, alloc_spread([size(side, key) for side, key in order])):
+                (self.dst_bufs if side else self.src_bufs)[key] = view(t, side, key[1])
+            self.placement = ("source/target buffers allocated alternately, strided over the free HBM by temporary "
+                              "spacer allocations (released before the timed region)")
         # synthetic state, generated in place: N(0, 0.02) fp32, PARAM = bf16(MASTER), all DP replicas identical
         columns = {}
         for pp in range(src.pp):
@@ -176,7 +171,7 @@ class World:
 
     def release(self):
         self.lv.liver_plan_destroy(self.plan)
-        self.src_bufs = self.dst_bufs = self.gaps = self.src_tab = self.dst_tab = None
+        self.src_bufs = self.dst_bufs = self.src_tab = self.dst_tab = None
         import gc
         gc.collect()
         self.torch.cuda.synchronize()
@@ -246,6 +241,7 @@ def main():
         extras["natural_placement_GBs"] = round(w.algo_bytes / (statistics.mean(ev) * 1e-3) / 1e9, 1)
         extras["natural_placement_ms"] = round(statistics.mean(ev), 4)
         extras["natural_placement"] = w.placement
+        extras["natural_placement_memory_classes"] = memory_classes(lv, torch, w)
         w.release()
         del w
 
@@ -357,25 +353,75 @@ def main():
         out["cpu_baseline"] = one
         out["cpu_baseline_all_cores"] = many
 
+    if not args.no_extras:
+        extras["timed_placement_memory_classes"] = memory_classes(lv, torch, world)   # overwrites the world: last use
     if not args.no_extras and args.workload == "llama7b":
-        # the other benchmark configurations, direct reshard, buffers in plain allocation order
+        # the other benchmark configurations, direct reshard, in both placements
         world.release()
         del world, src_tab, dst_tab, plan
         others = {}
         for name in OTHER_WORKLOADS:
-            w = World(lv, synth, torch, name, "natural")
-            _, ev = timed(torch, w.reshard, 20, 3)
-            ms = statistics.mean(ev)
-            others[name] = {"GBs": round(w.algo_bytes / (ms * 1e-3) / 1e9, 1), "ms": round(ms, 4),
-                            "frac_hbm_peak": round(w.algo_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                            "algorithmic_bytes": w.algo_bytes, "n_desc": w.info.n_desc, "placement": "plain allocation order"}
-            w.release()
-            del w
+            others[name] = {}
+            for place in ("natural", "spread"):
+                w = World(lv, synth, torch, name, place)
+                _, ev = timed(torch, w.reshard, 20, 3)
+                ms = statistics.mean(ev)
+                others[name].update({"algorithmic_bytes": w.algo_bytes, "n_desc": w.info.n_desc,
+                                     f"{place}_GBs": round(w.algo_bytes / (ms * 1e-3) / 1e9, 1), f"{place}_ms": round(ms, 4),
+                                     f"{place}_frac_hbm_peak": round(w.algo_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
+                w.release()
+                del w
+        extras["other_workloads_placements"] = {"natural": "plain allocation order", "spread": "alternating, strided over the free HBM"}
         extras["other_workloads_direct"] = others
     if extras:
         out["extras"] = extras
 
     print(json.dumps(out))
+
+
+def memory_classes(lv, torch, world, window=1 << 30):
+    """Which buffers of a world share a class of the device memory, found by timing: two windows filled in ONE
+    launch reach about 7.1 TB/s if they sit in different classes and about 5.7 TB/s if they share one (a write
+    stream confined to one class is capped there; profiles/placement.md).  The first `window` bytes of every
+    buffer are probed against one representative per class found so far.  OVERWRITES those bytes: call it on a
+    world whose contents are no longer needed."""
+    def rate(a, b):
+        best = 0.0
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            lv.liver_debug_bandwidth_probe(3, a, b, window, 256)
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, 2 * window / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        return best
+    refs, out, rates = [], {}, {"same": [], "other": []}
+    for side, bufs in (("source", world.src_bufs), ("target", world.dst_bufs)):
+        letters = ""
+        for key, t in bufs.items():
+            if t.numel() * t.element_size() < window:
+                letters += "-"
+                continue
+            found = None
+            for ci, ref in enumerate(refs):
+                if ref.data_ptr() == t.data_ptr():
+                    found = ci
+                    break
+                g = rate(t, ref)
+                same = g < 6400.0
+                rates["same" if same else "other"].append(g)
+                if same:
+                    found = ci
+                    break
+            if found is None:
+                refs.append(t)
+                found = len(refs) - 1
+            letters += "ABCDEFGH"[min(found, 7)]
+        out[side] = letters
+    out["how"] = (f"first {window >> 20} MiB of every buffer filled together with a representative of each class, in "
+                  f"allocation order; same class: {min(rates['same'], default=0):.0f}-{max(rates['same'], default=0):.0f} GB/s, "
+                  f"different: {min(rates['other'], default=0):.0f}-{max(rates['other'], default=0):.0f} GB/s")
+    return out
 
 
 def _column_used(lv, plan, src, rank):

@@ -367,7 +367,7 @@ int liver_reshard_static(const liver_plan_t* plan, const void* const* src_bufs, 
 
 int liver_debug_bandwidth_probe(int mode, const void* src, void* dst, size_t bytes, int grid, void* hip_stream) {
     const size_t tile_bytes = (size_t)liver::PROBE_TILE_UNITS * 16;
-    if (mode < 0 || mode > 2) return fail(LIVER_E_INVALID_ARG, "probe mode must be 0 (read), 1 (fill) or 2 (copy)");
+    if (mode < 0 || mode > 3) return fail(LIVER_E_INVALID_ARG, "probe mode must be 0 (read), 1 (fill), 2 (copy) or 3 (fill both)");
     if (!dst || (mode != 1 && !src)) return fail(LIVER_E_INVALID_ARG, "probe buffer is NULL");
     if ((uintptr_t)dst % 16 || (uintptr_t)src % 16) return fail(LIVER_E_INVALID_ARG, "buffers must be 16-byte aligned");
     if (bytes == 0 || bytes % tile_bytes) return fail(LIVER_E_INVALID_ARG, "probe size must be a positive multiple of 32 KiB");

@@ -249,22 +249,25 @@ __global__ __launch_bounds__(BLOCK) void liver_fused_kernel(const FusedArgs f) {
 
 // Reference dispatches for measurement: the plainest streaming kernels the chip can run (grid-stride over
 // tiles of PROBE_TILE_UNITS contiguous 16-byte units, PROBE_TILE_UNITS / BLOCK non-temporal accesses in flight per lane).
-// MODE 0 reads `a` (and stores one unit per workgroup into `b` so the loads stay), 1 fills `b`, 2 copies.
+// MODE 0 reads `a` (and stores one unit per workgroup into `b` so the loads stay), 1 fills `b`, 2 copies a -> b,
+// 3 fills BOTH `a` and `b` (n_tiles each) in one launch.
 template <int MODE>
-__global__ __launch_bounds__(BLOCK) void liver_probe_kernel(const u32x4* __restrict__ a, u32x4* __restrict__ b, uint64_t n_tiles) {
+__global__ __launch_bounds__(BLOCK) void liver_probe_kernel(u32x4* __restrict__ a, u32x4* __restrict__ b, uint64_t n_tiles) {
     constexpr int U = PROBE_TILE_UNITS / BLOCK;
     u32x4 acc = {1u, 2u, 3u, 4u};
-    for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        const uint64_t at0 = t * PROBE_TILE_UNITS + threadIdx.x;
+    const uint64_t total = MODE == 3 ? 2 * n_tiles : n_tiles;
+    for (uint64_t t = blockIdx.x; t < total; t += gridDim.x) {
+        const uint64_t at0 = (MODE == 3 && t >= n_tiles ? t - n_tiles : t) * PROBE_TILE_UNITS + threadIdx.x;
+        u32x4* out = MODE == 3 && t < n_tiles ? a : b;
         u32x4 v[U];
 #pragma unroll
-        for (int i = 0; i < U; ++i) v[i] = MODE == 1 ? acc : __builtin_nontemporal_load(a + at0 + (uint64_t)i * BLOCK);
+        for (int i = 0; i < U; ++i) v[i] = MODE == 1 || MODE == 3 ? acc : __builtin_nontemporal_load(a + at0 + (uint64_t)i * BLOCK);
         if (MODE == 0) {
 #pragma unroll
             for (int i = 0; i < U; ++i) acc ^= v[i];
         } else {
 #pragma unroll
-            for (int i = 0; i < U; ++i) __builtin_nontemporal_store(v[i], b + at0 + (uint64_t)i * BLOCK);
+            for (int i = 0; i < U; ++i) __builtin_nontemporal_store(v[i], out + at0 + (uint64_t)i * BLOCK);
         }
     }
     if (MODE == 0 && threadIdx.x == 0) b[blockIdx.x] = acc;  // lane 0's value: enough to keep every lane's loads
@@ -273,12 +276,13 @@ __global__ __launch_bounds__(BLOCK) void liver_probe_kernel(const u32x4* __restr
 // Both launchers report the status of THEIR launch (hipLaunchKernel's own return value): an error that
 // some earlier call of the thread left behind is neither returned nor cleared here.
 hipError_t launch_probe(int mode, const void* src, void* dst, uint64_t n_tiles, uint32_t grid, hipStream_t stream) {
-    const u32x4* a = (const u32x4*)src;
+    u32x4* a = (u32x4*)src;  // written by mode 3 only
     u32x4* o = (u32x4*)dst;
     void* kargs[] = {(void*)&a, (void*)&o, (void*)&n_tiles};
     const void* fn = mode == 0   ? (const void*)&liver_probe_kernel<0>
                      : mode == 1 ? (const void*)&liver_probe_kernel<1>
-                                 : (const void*)&liver_probe_kernel<2>;
+                     : mode == 2 ? (const void*)&liver_probe_kernel<2>
+                                 : (const void*)&liver_probe_kernel<3>;
     return hipLaunchKernel(fn, dim3(grid), dim3(BLOCK), kargs, 0, stream);
 }
 

@@ -1,0 +1,33 @@
+"""Where a caller's buffers sit in HBM decides what any copy between them can reach on MI355X.
+
+Measured (profiles/placement.md): device memory falls into three classes of 96 GiB (the stack levels of the
+12-high HBM3E stacks, as far as a program can tell); a write stream confined to ONE class is capped near 5.7 TB/s
+and a copy whose targets all sit in one class near 5.6 TB/s, while targets that span two or three classes are
+written at 7.1 TB/s and copied at 6.3-6.5 TB/s.  The first large allocations of a process are physically
+contiguous, so "all source buffers, then all target buffers" puts each world into one class.
+
+alloc_spread() is the caller-side recipe the benchmark uses: it strides a list of allocations over the free
+memory with TEMPORARY spacer allocations, which are released again before it returns (the buffers keep their
+place), so neighbouring buffers -- and with them the bytes a reshard writes at any one time -- land in
+different classes.  It only places buffers; it is not part of the data path."""
+from __future__ import annotations
+
+from typing import List, Sequence
+
+import torch
+
+
+def alloc_spread(sizes: Sequence[int], device: str = "cuda", reserve: int = 14 << 30) -> List[torch.Tensor]:
+    """uint8 device tensors of the given sizes, in the given order, spread evenly over the currently free device
+    memory (minus `reserve` bytes).  Interleave source and target sizes in `sizes` to mix both worlds."""
+    sizes = [int(n) for n in sizes]
+    free, _ = torch.cuda.mem_get_info()
+    gap = max(0, (free - sum(sizes) - reserve) // max(1, len(sizes))) & ~((2 << 20) - 1)
+    out, spacers = [], []
+    for n in sizes:
+        out.append(torch.empty(n, dtype=torch.uint8, device=device))
+        if gap:
+            spacers.append(torch.empty(gap, dtype=torch.uint8, device=device))
+    del spacers
+    torch.cuda.empty_cache()          # the spacers go back to the driver; the buffers stay where they are
+    return out

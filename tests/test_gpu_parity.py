@@ -462,6 +462,12 @@ def test_bandwidth_probe_kernels(grid):
     lv.liver_debug_bandwidth_probe(0, src, dst, n, grid)
     torch.cuda.synchronize()
     assert torch.equal(src, keep) and (dst[min(grid, n // 16) * 16:] == 0x5A).all()
+    two = torch.full((n + 4096,), 0x5A, dtype=torch.uint8, device="cuda")
+    dst.fill_(0x5A)
+    lv.liver_debug_bandwidth_probe(3, two, dst, n, grid)     # fills both windows, nothing after either
+    torch.cuda.synchronize()
+    for t in (two, dst):
+        assert torch.equal(t[:n].view(torch.int32), want) and (t[n:] == 0x5A).all()
 
 
 def test_fused_cast_on_all_2_32_bit_patterns():

@@ -473,7 +473,7 @@ def test_plan_of_a_source_rank_that_contributes_nothing():
 def test_bandwidth_probe_rejects_bad_arguments_before_any_launch():
     """Argument errors of the measurement aid are found on the host (no GPU needed, nothing is launched)."""
     ok = dict(mode=2, src=4096, dst=1 << 20, nbytes=32768, grid=8)
-    for bad in (dict(mode=3), dict(mode=-1), dict(src=0), dict(dst=0), dict(src=4100), dict(dst=(1 << 20) + 8), dict(nbytes=0),
+    for bad in (dict(mode=4), dict(mode=-1), dict(src=0), dict(dst=0), dict(src=4100), dict(dst=(1 << 20) + 8), dict(nbytes=0),
                 dict(nbytes=32768 + 16), dict(grid=0), dict(grid=65537), dict(mode=0, grid=4096)):
         kw = dict(ok, **bad)
         with pytest.raises(lv.LiverError) as e:
