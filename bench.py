@@ -133,9 +133,20 @@ class World:
                 for key in keys:
                     bufs[key] = view(torch.empty(size(side, key), dtype=torch.uint8, device="cuda"), side, key[1])
             self.placement = "all source buffers, then all target buffers, in plain allocation order (no gaps)"
+        elif placement == "targets_spread":
+            # the source world as a training job holds it (plain order); the target buffers, which are allocated
+            # when the reconfiguration is prepared, strided over the remaining free HBM by temporary spacer
+            # allocations (released again before the first launch): paper_2605_22014_amd.placement
+            from paper_2605_22014_amd.placement import alloc_spread
+            for key in src_keys:
+                self.src_bufs[key] = view(torch.empty(size(0, key), dtype=torch.uint8, device="cuda"), 0, key[1])
+            for key, t in zip(dst_keys, alloc_spread([size(1, key) for key in dst_keys])):
+                self.dst_bufs[key] = t
+            self.placement = ("source buffers in plain allocation order; target buffers strided over the remaining free HBM "
+                              "by temporary spacer allocations (released before the timed region)")
         else:
             # source and target buffers allocated ALTERNATELY and strided over the whole free HBM by temporary
-            # spacer allocations (released again before the first launch): paper_2605_22014_amd.placement
+            # spacer allocations (released again before the first launch)
             order = []
             for i in range(max(len(src_keys), len(dst_keys))):
                 order += [(0, src_keys[i])] if i < len(src_keys) else []
@@ -204,7 +215,8 @@ def main():
     ap.add_argument("--grid", type=int, default=0)
     ap.add_argument("--tile-order", type=int, default=-1, help="-1 = library default")
     ap.add_argument("--cache-hints", type=int, default=-1, help="-1 = library default")
-    ap.add_argument("--placement", default="spread", choices=("spread", "natural"), help="where the timed run's buffers sit")
+    ap.add_argument("--placement", default="targets_spread", choices=("targets_spread", "alternating", "natural"),
+                    help="where the timed run's buffers sit")
     ap.add_argument("--no-natural-leg", action="store_true",
                     help="skip the leg that times the same reshard with the buffers in plain allocation order first")
     ap.add_argument("--no-extras", action="store_true", help="skip the staged / derive / plain-copy / other-workload legs")
@@ -235,7 +247,7 @@ def main():
     # ---- first thing in the process: the same reshard with the buffers where a plain allocation sequence puts
     # them.  Where the caller's buffers sit in HBM changes the bandwidth of any copy on this part (measured, see
     # profiles/placement.md), and the first large allocations of a process are the least favourable case.
-    if not args.no_natural_leg and args.placement == "spread":
+    if not args.no_natural_leg and args.placement != "natural":
         w = World(lv, synth, torch, args.workload, "natural", launch)
         _, ev = timed(torch, w.reshard, max(5, args.steps // 2), args.warmup)
         extras["natural_placement_GBs"] = round(w.algo_bytes / (statistics.mean(ev) * 1e-3) / 1e9, 1)
@@ -327,7 +339,27 @@ def main():
         _, k = timed(torch, unpack_only, 3, 1)
         extras["unpack_kernel_GBs"] = round((info.stream_bytes + info.bytes_written) / (statistics.mean(k) * 1e-3) / 1e9, 1)
         extras["n_chunks"] = nch
-        del staging
+        # the same stream with unpack(k-1) and pack(k) fused into one launch (two staging chunks), and both forms
+        # again through chunks a quarter of the size
+        staging2 = torch.empty(cfg["chunk_bytes"], dtype=torch.uint8, device="cuda")
+        w, _ = timed(torch, lambda: lv.liver_reshard_staged_fused(plan, src_tab, dst_tab, staging, staging2), 3, 1)
+        extras["staged_fused_ms"] = round(w, 3)
+        extras["staged_fused_end_to_end_GBs"] = round(algo_bytes / (w * 1e-3) / 1e9, 1)
+        small = cfg["chunk_bytes"] // 4
+        splan = lv.liver_plan_create(world.spec, world.src, world.dst, small)
+        sn = lv.liver_plan_info(splan).n_chunks
+
+        def staged_small():
+            for c in range(sn):
+                lv.liver_pack(splan, c, src_tab, staging[:small])
+                lv.liver_unpack(splan, c, staging[:small], dst_tab)
+        w, _ = timed(torch, staged_small, 3, 1)
+        extras["staged_quarter_chunks_ms"] = round(w, 3)
+        w, _ = timed(torch, lambda: lv.liver_reshard_staged_fused(splan, src_tab, dst_tab, staging[:small], staging2[:small]), 3, 1)
+        extras["staged_quarter_chunks_fused_ms"] = round(w, 3)
+        extras["staged_quarter_chunk_bytes"] = small
+        lv.liver_plan_destroy(splan)
+        del staging, staging2
         if 0 in cfg["kinds"] and 1 in cfg["kinds"]:
             dplan = lv.liver_plan_create(world.spec, world.src, lv.Layout(**dict(world.dst_kw, derive_bf16=True)), cfg["chunk_bytes"])
             dinfo = lv.liver_plan_info(dplan)
@@ -362,7 +394,7 @@ def main():
         others = {}
         for name in OTHER_WORKLOADS:
             others[name] = {}
-            for place in ("natural", "spread"):
+            for place in ("natural", "targets_spread"):
                 w = World(lv, synth, torch, name, place)
                 _, ev = timed(torch, w.reshard, 20, 3)
                 ms = statistics.mean(ev)
@@ -371,7 +403,8 @@ def main():
                                      f"{place}_frac_hbm_peak": round(w.algo_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
                 w.release()
                 del w
-        extras["other_workloads_placements"] = {"natural": "plain allocation order", "spread": "alternating, strided over the free HBM"}
+        extras["other_workloads_placements"] = {"natural": "plain allocation order",
+                                                "targets_spread": "sources in plain order, targets strided over the free HBM"}
         extras["other_workloads_direct"] = others
     if extras:
         out["extras"] = extras
@@ -390,7 +423,7 @@ def memory_classes(lv, torch, world, window=1 << 30):
         for _ in range(3):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            lv.liver_debug_bandwidth_probe(3, a, b, window, 256)
+            lv.liver_debug_bandwidth_probe(3, a, b, window, 8192)
             e1.record()
             torch.cuda.synchronize()
             best = max(best, 2 * window / (e0.elapsed_time(e1) * 1e-3) / 1e9)

@@ -270,6 +270,40 @@ def test_fused_staged_reshard_small_and_odd(derive):
     check_against(run_fused(plan, to_dev(w)), oracle.reshard_state(ODD, osrc, odst, w, derive_bf16=derive), plan, "fused filtered")
 
 
+def test_spread_allocation_helper_places_usable_buffers():
+    """placement.alloc_spread: the buffers it returns are distinct, of the sizes asked for, far apart, and a reshard
+    between them gives the oracle's bits (the spacers it used are gone: the free memory is back)."""
+    from paper_2605_22014_amd.placement import alloc_spread
+    cfg, spec, src, dst = cfg_objects("tiny_gpt")
+    print("spread allocation helper", flush=True)
+    world = make_world(spec, src, synth.logical_state(oracle.logical_tensors(spec), 9, cfg["dist"]))
+    want = oracle.reshard_state(spec, src, dst, world)
+    plan = _plan(spec, src, dst, cfg["chunk_bytes"])
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free0, _ = torch.cuda.mem_get_info()
+    keys = [(0, k) for k in world] + [(1, (r, k)) for r in range(dst.n_ranks) for k in range(4)]
+    sizes = [lv.liver_plan_buffer_bytes(plan, side, *key) for side, key in keys]
+    big = [768 << 20] * 6                            # large buffers (their own device allocations) show the stride
+    bufs = alloc_spread(sizes + big)
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < sum(sizes + big) + (len(sizes) + 8) * (20 << 20), "the temporary spacers must be released"
+    assert [t.numel() for t in bufs] == sizes + big and len({t.data_ptr() for t in bufs}) == len(bufs)
+    ptrs = sorted(t.data_ptr() for t in bufs[len(sizes):])
+    assert ptrs[-1] - ptrs[0] > 32 << 30, "large buffers should be strided over the free memory"
+    bufs = bufs[:len(sizes)]
+    src_dev, out = {}, {}
+    for (side, key), t in zip(keys, bufs):
+        if side == 0:
+            t.copy_(torch.from_numpy(world[key].view(np.uint8)))
+            src_dev[key] = t
+        else:
+            out[key] = t.fill_(0xA5).view(torch.int16 if key[1] == 0 else torch.int32)
+    lv.liver_reshard(plan, src_dev, out)
+    torch.cuda.synchronize()
+    check_against(out, want, plan, "buffers from alloc_spread")
+
+
 def test_identity_layout_is_a_plain_copy():
     """Same world on both sides: the target equals the source (with zero padding in the source)."""
     cfg, spec, src, dst = cfg_objects("tiny_gpt")
