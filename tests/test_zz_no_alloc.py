@@ -85,3 +85,24 @@ def test_static_staging_refuses_a_larger_chunk_and_bad_tables_before_any_launch(
     lv.liver_reshard_static(plan, dev, out)
     torch.cuda.synchronize()
     check_against(out, oracle.reshard_state(spec, src, dst, world), plan, "after the refusals")
+
+
+def test_static_staging_under_hip_graph_capture():
+    """What the entry point is for: a caller under HIP-graph capture may not allocate.  The whole staged reshard
+    through the library's array is captured once and replayed three times, with eager work in between."""
+    print("static staging: graph capture", flush=True)
+    plan, dev, want = _world("tiny_gpt", 1 << 20, synth.SEED_BASE + 2)
+    out = alloc_dst(plan)
+    from paper_2605_22014_amd._binding import make_table
+    st, dt = make_table(dev, plan.src.n_ranks), make_table(out, plan.dst.n_ranks)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lv.liver_reshard_static(plan, st, dt)
+    for replay in range(3):
+        for t in out.values():
+            t.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        check_against(out, want, plan, f"static staging, graph replay {replay}")
