@@ -145,9 +145,13 @@ def test_gpt2_small_derive(gpt2):
 
 
 @pytest.mark.parametrize("grid,order,hints", [(1, 0, 0), (7, 1, 3), (256, 0, 1), (2048, 1, 2), (65536, 0, 3), (0, 1, 0),
-                                              (256, 2, 3), (0, 2, -1), (5, 2, 0), (4096, 2, -1)])
+                                              (256, 2, 3), (0, 2, -1), (5, 2, 0), (4096, 2, -1),
+                                              (0, 3, -1), (256, 108, 3), (97, 108, 0), (60, 108, 3), (2048, 132, 1),
+                                              (1000, 102, 2), (65536, 1124, 3), (256, 356, 3)])
 def test_gpt2_small_launch_shapes(gpt2, grid, order, hints):
-    """The result does not depend on grid size, tile order or cache hints."""
+    """The result does not depend on grid size, tile order (one range per workgroup, interleaved, scattered, teams
+    of 2 ... 1024 workgroups incl. grids that are not a multiple of the team width and grids too small for teams)
+    or cache hints."""
     cfg, spec, src, dst, world, want, dev = gpt2
     print(f"gpt2_small launch grid {grid} order {order} hints {hints}", flush=True)
     plan = _plan(spec, src, dst, cfg["chunk_bytes"], only_tp=1) if grid == 1 else _plan(spec, src, dst, cfg["chunk_bytes"])
@@ -337,6 +341,11 @@ def test_many_buffers_split_into_passes():
     dev = to_dev(world)
     check_against(run_direct(plan, dev), want, plan, "direct, multi-pass")
     check_against(run_staged(plan, dev), want, plan, "staged")
+    check_against(run_fused(plan, dev), want, plan, "staged, fused launches")
+    one_chunk = _plan(spec, src, dst, 1 << 28)                 # the whole stream in ONE chunk: its pack and unpack need
+    assert lv.liver_plan_info(one_chunk).n_chunks == 1         # several passes each, which the fused entry runs unfused
+    check_against(run_staged(one_chunk, dev), want, one_chunk, "staged, multi-pass chunk")
+    check_against(run_fused(one_chunk, dev), want, one_chunk, "fused entry, multi-pass chunk")
 
 
 def test_staged_loop_in_hip_graph():
