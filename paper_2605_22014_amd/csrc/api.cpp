@@ -1,4 +1,4 @@
-// The C ABI: plan lifetime, inspection, and the three data calls.
+// The C ABI: plan lifetime, inspection, the three data calls and the whole-pipeline forms built on them.
 #include <hip/hip_runtime_api.h>
 
 #include <cstring>
