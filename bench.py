@@ -406,6 +406,9 @@ def main():
         extras["other_workloads_placements"] = {"natural": "plain allocation order",
                                                 "targets_spread": "sources in plain order, targets strided over the free HBM"}
         extras["other_workloads_direct"] = others
+    out["paper_context"] = ("context only, other hardware and a different quantity: on 32 A800 80 GB PCIe GPUs (PCIe Gen4 + 200 Gb/s "
+                            "InfiniBand) the paper's reconfiguration is 14-23x faster than checkpoint/restart (minutes -> 2-6 s of "
+                            "downtime); its transfer-and-combine phase moves ~28 GB in ~2 s for a 14B model, network included")
     if extras:
         out["extras"] = extras
 
