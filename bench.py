@@ -101,6 +101,29 @@ def refresh_traffic(fetch_csv, write_csv, workload):
     print(json.dumps(table["workloads"][workload]))
 
 
+class Scrub:
+    """Released device memory is scrubbed by the driver in the background (about 30 GB/s; a copy that runs
+    meanwhile loses about 1 %).  The benchmark's own legs release up to 190 GB right before the next leg's
+    buffers are timed, which no reconfiguration does (its target buffers are allocated during preparation, its
+    old world is freed after the switch): every timed leg first waits until the scrubbing of what the benchmark
+    itself released must be over.  The waiting is idle time, not warm-up."""
+    until = 0.0
+    waited = 0.0
+
+    @classmethod
+    def released(cls, nbytes):
+        from paper_2605_22014_amd.placement import scrub_seconds
+        cls.until = max(cls.until, time.perf_counter()) + scrub_seconds(nbytes)
+
+    @classmethod
+    def wait(cls):
+        left = cls.until - time.perf_counter()
+        if left > 0:
+            time.sleep(left)
+            cls.waited += left
+        return max(left, 0.0)
+
+
 class World:
     """Plan + source and target buffers of one workload, resident in HBM."""
 
@@ -137,11 +160,14 @@ class World:
             # the source world as a training job holds it (plain order); the target buffers, which are allocated
             # when the reconfiguration is prepared, strided over the remaining free HBM by temporary spacer
             # allocations (released again before the first launch): paper_2605_22014_amd.placement
-            from paper_2605_22014_amd.placement import alloc_spread
+            from paper_2605_22014_amd.placement import alloc_spread, spacer_gap
             for key in src_keys:
                 self.src_bufs[key] = view(torch.empty(size(0, key), dtype=torch.uint8, device="cuda"), 0, key[1])
-            for key, t in zip(dst_keys, alloc_spread([size(1, key) for key in dst_keys])):
+            sizes = [size(1, key) for key in dst_keys]
+            spacers = len(sizes) * spacer_gap(sizes)
+            for key, t in zip(dst_keys, alloc_spread(sizes)):
                 self.dst_bufs[key] = t
+            Scrub.released(spacers)
             self.placement = ("source buffers in plain allocation order; target buffers strided over the remaining free HBM "
                               "by temporary spacer allocations (released before the timed region)")
         else:
@@ -151,9 +177,12 @@ class World:
             for i in range(max(len(src_keys), len(dst_keys))):
                 order += [(0, src_keys[i])] if i < len(src_keys) else []
                 order += [(1, dst_keys[i])] if i < len(dst_keys) else []
-            from paper_2605_22014_amd.placement import alloc_spread
-            for (side, key), t in zip(order, alloc_spread([size(side, key) for side, key in order])):
+            from paper_2605_22014_amd.placement import alloc_spread, spacer_gap
+            sizes = [size(side, key) for side, key in order]
+            spacers = len(sizes) * spacer_gap(sizes)
+            for (side, key), t in zip(order, alloc_spread(sizes)):
                 (self.dst_bufs if side else self.src_bufs)[key] = view(t, side, key[1])
+            Scrub.released(spacers)
             self.placement = ("source/target buffers allocated alternately, strided over the free HBM by temporary "
                               "spacer allocations (released before the timed region)")
         # synthetic state, generated in place: N(0, 0.02) fp32, PARAM = bf16(MASTER), all DP replicas identical
@@ -176,11 +205,13 @@ class World:
         self.src_tab = make_table(self.src_bufs, src.n_ranks, plan, 0)
         self.dst_tab = make_table(self.dst_bufs, dst.n_ranks, plan, 1)
         torch.cuda.synchronize()
+        self.idle_before_timing_s = Scrub.wait()
 
     def reshard(self):
         self.lv.liver_reshard(self.plan, self.src_tab, self.dst_tab)
 
     def release(self):
+        Scrub.released(sum(t.numel() * t.element_size() for bufs in (self.src_bufs, self.dst_bufs) for t in bufs.values()))
         self.lv.liver_plan_destroy(self.plan)
         self.src_bufs = self.dst_bufs = self.src_tab = self.dst_tab = None
         import gc
@@ -278,7 +309,10 @@ def main():
                    "kinds": list(cfg["kinds"]), "mode": "direct (liver_reshard)", "algorithmic_bytes": algo_bytes,
                    "n_desc": info.n_desc, "plan_ms": round(world.plan_ms, 2), "table_bytes_device": info.table_bytes_device,
                    "launch": {"grid": args.grid, "tile_order": args.tile_order, "cache_hints": args.cache_hints},
-                   "placement": world.placement},
+                   "placement": world.placement,
+                   "idle_before_timing_s": round(world.idle_before_timing_s, 1),
+                   "idle_reason": "memory the benchmark itself released just before (plain-order leg, spacers) is scrubbed "
+                                  "by the driver in the background at about 30 GB/s; the timed region starts when that is over"},
         "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 2),
         "roofline": {"bound": "hbm", "kernel": "liver_copy_kernel (direct reshard)", "achieved": round(kern_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(kern_gbs / HBM_PEAK_GBS, 4),

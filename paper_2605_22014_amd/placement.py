@@ -9,7 +9,12 @@ contiguous, so "all source buffers, then all target buffers" puts each world int
 alloc_spread() is the caller-side recipe the benchmark uses: it strides a list of allocations over the free
 memory with TEMPORARY spacer allocations, which are released again before it returns (the buffers keep their
 place), so neighbouring buffers -- and with them the bytes a reshard writes at any one time -- land in
-different classes.  It only places buffers; it is not part of the data path."""
+different classes.  It only places buffers; it is not part of the data path.
+
+Released device memory is scrubbed by the driver in the background (measured: about 30 GB/s, i.e. about 3 s for
+the spacers of a 94 GB world), and copies that run meanwhile lose about 1 %: allocate the target buffers a few
+seconds before the reshard, as a reconfiguration's preparation phase does anyway.  scrub_seconds() is that
+estimate."""
 from __future__ import annotations
 
 from typing import List, Sequence
@@ -17,12 +22,26 @@ from typing import List, Sequence
 import torch
 
 
+SCRUB_BYTES_PER_SECOND = 30e9      # background scrubbing of released device memory, measured on MI355X / ROCm 7.2
+
+
+def scrub_seconds(released_bytes: int) -> float:
+    """How long the driver keeps scrubbing `released_bytes` of freed device memory in the background."""
+    return released_bytes / SCRUB_BYTES_PER_SECOND + 0.5 if released_bytes > 0 else 0.0
+
+
+def spacer_gap(sizes: Sequence[int], reserve: int = 14 << 30) -> int:
+    """Size of each temporary spacer alloc_spread would put after each of `sizes` right now."""
+    free, _ = torch.cuda.mem_get_info()
+    return max(0, (free - sum(int(n) for n in sizes) - reserve) // max(1, len(sizes))) & ~((2 << 20) - 1)
+
+
 def alloc_spread(sizes: Sequence[int], device: str = "cuda", reserve: int = 14 << 30) -> List[torch.Tensor]:
     """uint8 device tensors of the given sizes, in the given order, spread evenly over the currently free device
-    memory (minus `reserve` bytes).  Interleave source and target sizes in `sizes` to mix both worlds."""
+    memory (minus `reserve` bytes).  Interleave source and target sizes in `sizes` to mix both worlds.  The
+    spacers it releases (len(sizes) * spacer_gap(sizes) bytes) are scrubbed for scrub_seconds() afterwards."""
     sizes = [int(n) for n in sizes]
-    free, _ = torch.cuda.mem_get_info()
-    gap = max(0, (free - sum(sizes) - reserve) // max(1, len(sizes))) & ~((2 << 20) - 1)
+    gap = spacer_gap(sizes, reserve)
     out, spacers = [], []
     for n in sizes:
         out.append(torch.empty(n, dtype=torch.uint8, device=device))
