@@ -3,14 +3,19 @@
 // One kernel serves pack, unpack and the direct reshard (LiveR, Section 4.6.2 and
 // Algorithm 1: the sender cuts each task's slice out of its shard, the receiver
 // assembles the slices into the new shard): each of the three is a list of
-// strided 2-D pieces, rows x run, A -> B.  The work is pure
-// HBM streaming, so the design is about memory, not arithmetic:
+// strided 2-D pieces, rows x run, A -> B (a second kernel runs two such lists
+// in one launch for the fused staged pipeline).  The work is pure HBM
+// streaming, so the design is about memory, not arithmetic:
 //   * a piece is cut into tiles of TILE_UNITS 16-byte units (64 KiB); a tile is
 //     what one workgroup moves at a time, so 256 compute units stay evenly loaded
 //     whatever the mix of 4 KiB norm vectors and 100 MB matrices;
 //   * persistent workgroups: each walks its tiles and advances through the
 //     descriptor table by itself (one binary search per workgroup, then
 //     sequential), all descriptor reads are wave-uniform;
+//   * tiles go to workgroups in teams: a team of 8 or 32 workgroups, all on one
+//     XCD (team = workgroup id mod team count, and consecutive ids go round the 8
+//     XCDs), owns one contiguous range of tiles and interleaves inside it, so each
+//     XCD's L2 sees a few wide sequential streams;
 //   * every lane moves 16 bytes per access (global_load/store_dwordx4), 64 lanes
 //     cover 1 KiB contiguous, 8 independent loads are in flight per lane before
 //     the first store; the fused cast reads 16 B of fp32 once and writes the
