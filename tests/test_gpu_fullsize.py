@@ -158,7 +158,8 @@ def _planned_bytes(cfg, only, ospec, odst, names):
 
 def _run_complete(name):
     """Direct reshard compared with the oracle on EVERY planned target element, group by group; then the staged
-    path into a second set of target buffers, compared with the verified direct result on the device."""
+    path, the fused staged entry and derive mode into a second set of target buffers, each compared with the
+    verified direct result on the device."""
     import time
     print(f"{name}: generating state in HBM", flush=True)
     cfg, only, ospec, osrc, odst, plan, src, dst, src_bufs = _setup(name)
@@ -190,9 +191,33 @@ def _run_complete(name):
     torch.cuda.synchronize()
     for key in dst_bufs:
         assert torch.equal(dst_bufs[key], staged[key]), ("staged differs from the verified direct result", key)
+
+    def refill():
+        for key, t in staged.items():
+            t.fill_(-23131 if key[1] == 0 else -1515870811)
+    print(f"{name}: fused staged entry", flush=True)
+    refill()
+    staging2 = torch.empty_like(staging)
+    lv.liver_reshard_staged_fused(plan, src_bufs, staged, staging, staging2)
+    torch.cuda.synchronize()
+    for key in dst_bufs:
+        assert torch.equal(dst_bufs[key], staged[key]), ("fused staged differs from the verified direct result", key)
+    del staging, staging2
+    if 0 in cfg["kinds"] and 1 in cfg["kinds"]:
+        # the generated state holds PARAM = bf16(MASTER) (torch's conversion), so re-deriving the bf16 weights from
+        # the fp32 master weights in the same pass must give the very bytes the copy gave, for every element
+        print(f"{name}: derive mode (fused fp32 -> bf16 cast)", flush=True)
+        dplan = lv.liver_plan_create(lv.ModelSpec(**cfg["spec"]), src,
+                                     lv.Layout(pad_multiple=cfg["pad_multiple"], kinds=tuple(cfg["kinds"]), derive_bf16=True,
+                                               **{"only_" + k: v for k, v in only.items()}, **cfg["dst"]), cfg["chunk_bytes"])
+        refill()
+        lv.liver_reshard(dplan, src_bufs, staged)
+        torch.cuda.synchronize()
+        for key in dst_bufs:
+            assert torch.equal(dst_bufs[key], staged[key]), ("derive mode differs from the verified copy result", key)
     for key, t in src_bufs.items():          # source world untouched
         assert int(t.view(torch.int16 if key[1] == 0 else torch.int32).sum(dtype=torch.int64)) == sums[key], key
-    print(f"{name}: staged ok (every element equal to the direct result)", flush=True)
+    print(f"{name}: staged, fused-staged and derive results equal the direct result on every element", flush=True)
 
 
 def _run(name, names):
