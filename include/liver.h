@@ -233,8 +233,8 @@ int liver_plan_desc(const liver_plan_t* plan, int list, int64_t i, liver_desc_t*
  * tile_order 0 = each workgroup walks one contiguous range of tiles, 1 = workgroups interleave tile by tile,
  * 2 = groups of up to 64 tiles visited in a scattered (multiplicative-permutation) order, 3 = teams: 8 or 32
  * workgroups (by launch size) share one contiguous range and interleave inside it, a team's members sitting on
- * one XCD; 100 + w = teams of w workgroups (2 <= w <= 1024; the grid is rounded down to a multiple of w, and a
- * launch with fewer than 8 teams runs as order 0); -1 = default (teams);
+ * one XCD (a launch too small for 8 teams runs as order 0); 100 + w = teams of w workgroups (2 <= w <= 1024; the
+ * grid is rounded down to a multiple of w; a grid smaller than w runs as order 0); -1 = default (teams);
  * cache_hints bit 0 = non-temporal loads, bit 1 = non-temporal stores, -1 =
  * default (direct: both; pack: loads only; unpack: stores only, so that the
  * staging chunk may stay cache-resident).  Not thread-safe against concurrent

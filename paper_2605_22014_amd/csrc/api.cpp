@@ -83,7 +83,8 @@ int launch_passes(const liver_plan* plan, const liver::List& list, uint32_t p0, 
         }
         if (order >= 3) {
             const uint32_t width = order >= 100 ? (uint32_t)order - 100u : pass.n_tiles >= (1u << 20) ? 8u : 32u;
-            if (width >= 2 && grid / width >= 8) {  // else: too few workgroups for teams, one range each (order 0)
+            // the library's own choice wants at least one team per XCD; an explicit width only has to fit the grid
+            if (width >= 2 && grid / width >= (order >= 100 ? 1u : 8u)) {  // else: one range per workgroup (order 0)
                 grid -= grid % width;
                 args.tile_order = 3, args.group = width;
             }
